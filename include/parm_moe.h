@@ -1,0 +1,188 @@
+/*
+ * parm_moe.h -- C ABI of the per-GPU compute of one rank of a Parm MoE layer on MI355X (gfx950).
+ *
+ * The layer is the one of Section II-A of the Parm paper ("Mixture-of-Experts Layer"): a
+ * gating function (one linear layer, softmax, top-k) builds G in R^{E x T x M}, expert i
+ * processes G[i,:,:] with two FFN matrices (M,H) and (H,M) around an activation, and the
+ * expert outputs are combined back to token order.  Parm (Section III) runs it under
+ * MP+EP+ESP: the MP group splits the tokens on entry (PauseMP, schedule S1), the experts are
+ * spread over N_EP ranks and each expert's hidden dimension over N_ESP shards, and two
+ * EP&ESP-AlltoAlls sit between dispatch / expert FFN / combine.  This library is what ONE
+ * rank computes between those collectives, forward and backward.  It performs no
+ * communication.
+ *
+ * Notation (Table 1 of the paper): S tokens gated by this rank (= B*L/N_MP), M embedding
+ * size, H expert hidden size, E experts in total, k experts per token, f capacity factor,
+ * C = the paper's T, rows per expert.  G = E/N_EP local experts, n_src = N_EP*N_ESP peers
+ * that send this rank a [G, C, M] chunk each, H_l = H/N_ESP.
+ *
+ * Conventions for every entry point
+ *   - All tensor pointers are DEVICE pointers to dense row-major memory owned by the caller,
+ *     16-byte aligned.  The library allocates nothing and keeps no state between calls;
+ *     scratch memory is a caller-supplied workspace `ws` of at least the size the matching
+ *     *_workspace_bytes() helper returns (ws may be NULL when that size is 0).
+ *   - `dtype` is MOE_F32 or MOE_BF16 and names the storage type of activations and expert
+ *     weights.  Gate weights, logits, combine weights and their gradients are always fp32,
+ *     index tensors int32.  Accumulation is fp32 (fp64 for the gate logits).
+ *   - Work is enqueued on `stream` (a hipStream_t passed as void*, NULL = default stream);
+ *     no call synchronises with the host.  Outputs are fully overwritten, never accumulated,
+ *     unless stated.
+ *   - Return value: MOE_OK, or a negative error.  Arguments are validated on the host before
+ *     anything is launched; on an error nothing was enqueued.  No exceptions, no aborts, no
+ *     output on stdout/stderr.
+ *   - MP and ESP are plain integers: (mp_idx, n_mp) picks this rank's block of the token
+ *     rows, (esp_idx, n_esp) picks the hidden slice [esp_idx*H/n_esp, (esp_idx+1)*H/n_esp)
+ *     of the FULL weight tensors W1 [G,M,H] and W2 [G,H,M].
+ *   - Limits: 1 <= k <= 8, k <= E <= 256, M % 8 == 0, H_l % 8 == 0 (bf16) or % 4 (fp32).
+ */
+#ifndef PARM_MOE_H
+#define PARM_MOE_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum { MOE_F32 = 0, MOE_BF16 = 1 };
+
+enum {
+  MOE_OK = 0,
+  MOE_EINVAL = -1,       /* a shape or argument is out of range / inconsistent */
+  MOE_EUNSUPPORTED = -2, /* valid in the paper's terms but outside this build's limits */
+  MOE_EALIGN = -3,       /* a pointer is not 16-byte aligned */
+  MOE_ELAUNCH = -4,      /* HIP reported an error when enqueuing */
+  MOE_EWORKSPACE = -5,   /* ws is NULL or ws_bytes is too small */
+  MOE_ENULL = -6         /* a required pointer is NULL */
+};
+
+/* Human-readable name of an error code (static storage, never NULL). */
+const char* moe_strerror(int err);
+
+/* Library ABI version (bumped when a signature changes). */
+int moe_abi_version(void);
+
+/* Expert capacity, Section II-A: T := k * f * B * L / E, for the S tokens this rank gates
+ * (schedule S1 gates the MP slice, Section III-B).  Rounded up, evaluated in double as
+ * ((k*S)*f)/E, at least 1.  Returns -1 on invalid arguments.  Host function. */
+int64_t moe_capacity(int64_t S, int E, int k, double f);
+
+/* ---------------------------------------------------------------------------------------
+ * Gate: Section II-A "Gating Function" (linear layer, softmax, top-k, capacity T) on the
+ * MP slice of Section III-B.
+ *
+ *   x         [S_total, M] activations (x_dtype), or NULL: then `logits` is an INPUT
+ *   Wg        [M, E] fp32 gate weight (ignored when x is NULL)
+ *   gate_bias [E] fp32 or NULL, added to the logits
+ *   S_total, n_mp, mp_idx: the rank gates rows [mp_idx*S, (mp_idx+1)*S), S = S_total/n_mp
+ *   norm_topk 1: weights = softmax over the k selected logits; 0: full-softmax probability
+ *             of each selected expert; -1: 1 when k >= 2, else 0
+ *   logits    [S, E] fp32, written (or read when x is NULL)
+ *   idx       [S, k] int32 out: selected experts, best first; equal logits -> lower index
+ *   w         [S, k] fp32 out: combine weights
+ *   slot      [S, k] int32 out: row of (t,j) in expert idx[t,j]'s block, -1 if dropped.
+ *             Slots are given choice-major (all first choices, then all second choices...)
+ *             and in token order within a choice; an expert keeps the first C.
+ *   inv       [E, C] int32 out: t*k+j of the occupant of each slot, -1 if empty
+ *   counts    [E] int32 out: assignments that asked for each expert (before capacity)
+ * --------------------------------------------------------------------------------------- */
+size_t moe_gate_workspace_bytes(int64_t S, int E, int k);
+
+int moe_gate_topk(const void* x, int x_dtype, const float* Wg, const float* gate_bias,
+                  int64_t S_total, int M, int E, int k, int64_t C,
+                  int mp_idx, int n_mp, int norm_topk,
+                  float* logits, int32_t* idx, int32_t* slot, float* w,
+                  int32_t* inv, int32_t* counts,
+                  void* ws, size_t ws_bytes, void* stream);
+
+/* ---------------------------------------------------------------------------------------
+ * Dispatch: Section II-A, "each row of G (G[i,:,:]) corresponds to the data that should be
+ * dispatched to expert i".  buf[e,c,:] = x[t,:] for the occupant (t,j) = inv[e,c], zeros for
+ * empty slots; with w != NULL rows are scaled by w[t,j] (fp32 multiply, rounded to dtype).
+ * buf [E,C,M] viewed [N_EP, G, C, M] is the send buffer of the EP&ESP-AlltoAll (Section
+ * III-C); the "Dump" that duplicates it N_ESP times is an alias of the same memory.
+ *   x [S, M] is the rank's own token block (already offset by the caller).
+ * --------------------------------------------------------------------------------------- */
+int moe_dispatch(const void* x, int dtype, int64_t S, int M, int E, int k, int64_t C,
+                 const int32_t* inv, const float* w, void* buf, void* stream);
+
+/* ---------------------------------------------------------------------------------------
+ * Expert FFN on one ESP shard: Section II-A "Experts" (weights (M,H) and (H,M) around an
+ * activation) with the hidden dimension split as in Y = sum_p W2^(p) f(W1^(p) X) (Section
+ * II-B "Model Parallelism", applied to experts by ESP).  f is the exact (erf) GeLU.
+ *
+ *   X  [n_src, G, C, M]  receive buffer of the EP&ESP-AlltoAll; local expert g owns the
+ *                        n_src*C rows X[:, g, :, :]
+ *   W1 [G, M, H], W2 [G, H, M]  full tensors; the shard uses columns / rows
+ *                        [esp_idx*H_l, (esp_idx+1)*H_l), H_l = H/n_esp
+ *   Z  [n_src, G, C, H_l] out: pre-activation X*W1 (saved for backward), dtype
+ *   Y  [n_src, G, C, M]   out: GeLU(Z)*W2 -- a partial sum when n_esp > 1
+ *
+ * Backward (chain rule of the above), given dY [n_src,G,C,M] and the saved Z:
+ *   dX  [n_src, G, C, M]  out
+ *   dW1 [G, M, H], dW2 [G, H, M]  FULL tensors; only the shard's columns / rows are written
+ *                        (overwritten, dtype, fp32 accumulation over all n_src*C rows)
+ * --------------------------------------------------------------------------------------- */
+size_t moe_ffn_workspace_bytes(int dtype, int n_src, int G, int64_t C, int M, int H, int n_esp,
+                               int backward);
+
+/* Tuning knob for the bf16 grouped GEMMs: 0 = choose the workgroup tile per GEMM from its
+ * tile count (default), 1 = always 128x128, 2 = always 256x256.  Process-wide; affects speed
+ * only, never results beyond fp32 summation order.  Returns MOE_EINVAL for other values. */
+int moe_ffn_set_tile(int tile);
+
+int moe_expert_ffn_fwd(const void* X, int dtype, const void* W1, const void* W2,
+                       int n_src, int G, int64_t C, int M, int H, int esp_idx, int n_esp,
+                       void* Z, void* Y, void* ws, size_t ws_bytes, void* stream);
+
+int moe_expert_ffn_bwd(const void* dY, const void* X, const void* Z, const void* W1,
+                       const void* W2, int dtype,
+                       int n_src, int G, int64_t C, int M, int H, int esp_idx, int n_esp,
+                       void* dX, void* dW1, void* dW2, void* ws, size_t ws_bytes, void* stream);
+
+/* ---------------------------------------------------------------------------------------
+ * Combine: Section II-A, the expert outputs [Q_1..Q_E] are combined into the (B,L,M) layer
+ * output; Section III-C, the N_ESP partial sums that come back through the second
+ * EP&ESP-AlltoAll are first added locally ("local combine").
+ *
+ *   Yret [n_part, E, C, M]  returned buffer(s); n_part = N_ESP partial sums (1 if summed)
+ *   y[t,:] = sum over j with slot[t,j] >= 0 of  w[t,j] * sum_p Yret[p, idx[t,j], slot[t,j], :]
+ *   w == NULL means unit weights: that is the backward of moe_dispatch (dx from dbuf).
+ *   Rows of tokens whose every choice was dropped are zero.
+ *
+ * Backward:  dYret [E, C, M] = w[t,j] * dy[t,:] at the occupant's slot, zeros at empty slots
+ *            (every partial sum receives this same gradient);
+ *            dw[t,j] = < dy[t,:], sum_p Yret[p, idx[t,j], slot[t,j], :] >, 0 if dropped.
+ * --------------------------------------------------------------------------------------- */
+int moe_combine_fwd(const void* Yret, int dtype, int n_part, int64_t S, int M, int E, int k,
+                    int64_t C, const int32_t* idx, const int32_t* slot, const float* w,
+                    void* y, void* stream);
+
+int moe_combine_bwd(const void* dy, const void* Yret, int dtype, int n_part,
+                    int64_t S, int M, int E, int k, int64_t C,
+                    const int32_t* idx, const int32_t* slot, const int32_t* inv, const float* w,
+                    void* dYret, float* dw, void* stream);
+
+/* ---------------------------------------------------------------------------------------
+ * Gate backward: chain rule through Section II-A's gating function with the selection held
+ * fixed.  dw -> dlogits (softmax over the selected k, or full softmax, as norm_topk says),
+ * dWg = x^T dlogits, dgate_bias = column sums of dlogits, dx = dlogits Wg^T.
+ *
+ *   x [S, M] the rank's token block; logits, idx, w as produced by moe_gate_topk
+ *   dlogits [S, E] fp32 out; dWg [M, E] fp32 out; dgate_bias [E] fp32 out or NULL
+ *   dx [S, M] (x_dtype): overwritten, or with dx_accumulate = 1 read and added to (so the
+ *   gate's share lands on top of the dispatch share computed by moe_combine_fwd(w=NULL))
+ * --------------------------------------------------------------------------------------- */
+size_t moe_gate_bwd_workspace_bytes(int64_t S, int M, int E);
+
+int moe_gate_bwd(const float* dw, const float* w, const int32_t* idx, const float* logits,
+                 const void* x, int x_dtype, const float* Wg,
+                 int64_t S, int M, int E, int k, int norm_topk,
+                 float* dlogits, float* dWg, float* dgate_bias,
+                 void* dx, int dx_accumulate, void* ws, size_t ws_bytes, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* PARM_MOE_H */

@@ -1,0 +1,404 @@
+// Gate of the MoE layer (Section II-A "Gating Function") on the rank's MP token slice
+// (Section III-B): logits = x Wg (+bias), top-k, combine weights, capacity slots.
+//
+// Kernels (wave64 throughout):
+//   gate_logits_small_e : E <= 16.  One wave owns 64/EC tokens; lanes split M, so x is read
+//                         once, coalesced, 16 B per lane.  fp64 accumulation, then a
+//                         halving cross-lane reduction that leaves lane i with output i.
+//   gate_logits_tiled   : any E.  64 tokens x 64 experts per block, LDS-staged K chunks,
+//                         4x4 register tile per thread, fp64 accumulation.
+//   gate_topk           : a group of W = pow2 >= E lanes per token; k rounds of an arg-max
+//                         butterfly (ties -> lower expert index); softmax weights; per-block
+//                         (choice, expert) histogram for the slot scan.
+//   gate_scan           : one wave per expert; exclusive scan of the histograms over token blocks and
+//                         over choices (choice-major priority), per-expert demand counts.
+//   gate_slots          : rank of each (token, choice) inside its block via wave ballots,
+//                         slot = base + rank if < C; inverse map; -1 tails of inv.
+// The logits are accumulated in fp64 and rounded once to fp32, so the routing decision is
+// taken on the same fp32 numbers a double-precision reference produces.
+#include "common.h"
+
+namespace {
+
+using namespace moe;
+
+constexpr int GATE_TB = 256;  // tokens per block in gate_topk / gate_slots (one per thread)
+
+template <bool BF16>
+__device__ __forceinline__ void load8(const void* base, int64_t elem_off, bool ok, float* f) {
+  if (!ok) {
+#pragma unroll
+    for (int i = 0; i < 8; ++i) f[i] = 0.f;
+    return;
+  }
+  if (BF16) {
+    const uint4 v = *reinterpret_cast<const uint4*>(reinterpret_cast<const bf16_t*>(base) + elem_off);
+    unpack_bf16x8(v, f);
+  } else {
+    const float4* p = reinterpret_cast<const float4*>(reinterpret_cast<const float*>(base) + elem_off);
+    const float4 a = p[0], b = p[1];
+    f[0] = a.x; f[1] = a.y; f[2] = a.z; f[3] = a.w; f[4] = b.x; f[5] = b.y; f[6] = b.z; f[7] = b.w;
+  }
+}
+
+__device__ __forceinline__ double shfl_xor_f64(double v, int mask) {
+  int lo = __double2loint(v), hi = __double2hiint(v);
+  lo = __shfl_xor(lo, mask, 64);
+  hi = __shfl_xor(hi, mask, 64);
+  return __hiloint2double(hi, lo);
+}
+
+// EC = experts held per lane (E <= EC), T = 64/EC tokens per wave.
+template <int EC, bool BF16, bool FULL>
+__global__ __launch_bounds__(64) void gate_logits_small_e(const void* __restrict__ x, const float* __restrict__ Wg,
+                                                           const float* __restrict__ bias, float* __restrict__ logits,
+                                                           int64_t S, int M, int E) {
+  constexpr int T = 64 / EC;
+  const int lane = threadIdx.x & 63;
+  const int64_t wave = (int64_t)blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6);
+  const int64_t t0 = wave * T;
+  if (t0 >= S) return;
+  double acc[T * EC];
+#pragma unroll
+  for (int i = 0; i < T * EC; ++i) acc[i] = 0.0;
+
+  for (int m0 = lane * 8; m0 < M; m0 += 512) {
+    float xf[T][8];
+#pragma unroll
+    for (int t = 0; t < T; ++t) load8<BF16>(x, (t0 + t) * (int64_t)M + m0, t0 + t < S, xf[t]);
+#pragma unroll
+    for (int mm = 0; mm < 8; ++mm) {
+      double wd[EC];
+      const float* wrow = Wg + (int64_t)(m0 + mm) * E;
+      if (FULL) {  // E == EC: rows of Wg are EC contiguous floats, 16-byte aligned
+#pragma unroll
+        for (int e = 0; e < EC; e += 4) {
+          const float4 q = *reinterpret_cast<const float4*>(wrow + e);
+          wd[e] = (double)q.x; wd[e + 1] = (double)q.y; wd[e + 2] = (double)q.z; wd[e + 3] = (double)q.w;
+        }
+      } else {
+#pragma unroll
+        for (int e = 0; e < EC; ++e) wd[e] = (e < E) ? (double)wrow[e] : 0.0;
+      }
+#pragma unroll
+      for (int t = 0; t < T; ++t) {
+        const double xd = (double)xf[t][mm];
+#pragma unroll
+        for (int e = 0; e < EC; ++e) acc[t * EC + e] = fma(xd, wd[e], acc[t * EC + e]);
+      }
+    }
+  }
+  // halving reduction over the 64 lanes: after the step with mask h, a lane whose bit h is
+  // set holds the upper half of the value list; at the end lane i holds the sum of value i.
+#pragma unroll
+  for (int h = 32; h >= 1; h >>= 1) {
+    const bool up = (lane & h) != 0;
+#pragma unroll
+    for (int i = 0; i < h; ++i) {
+      const double keep = up ? acc[i + h] : acc[i];
+      const double send = up ? acc[i] : acc[i + h];
+      acc[i] = keep + shfl_xor_f64(send, h);
+    }
+  }
+  const int t = lane / EC, e = lane % EC;
+  if (t0 + t < S && e < E) {
+    double v = acc[0];
+    if (bias) v += (double)bias[e];
+    logits[(t0 + t) * E + e] = (float)v;
+  }
+}
+
+// 64 tokens x 64 experts per block; thread (ty,tx) owns tokens ty*4..+4, experts tx*4..+4.
+template <bool BF16>
+__global__ __launch_bounds__(256) void gate_logits_tiled(const void* __restrict__ x, const float* __restrict__ Wg,
+                                                         const float* __restrict__ bias, float* __restrict__ logits,
+                                                         int64_t S, int M, int E) {
+  constexpr int KC = 32;
+  __shared__ float xs[KC][64 + 4];   // [k][token]
+  __shared__ float wsm[KC][64 + 4];  // [k][expert]
+  const int tid = threadIdx.x;
+  const int tx = tid & 15, ty = tid >> 4;
+  const int64_t t0 = (int64_t)blockIdx.x * 64;
+  const int e0 = blockIdx.y * 64;
+  double acc[4][4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+#pragma unroll
+    for (int j = 0; j < 4; ++j) acc[i][j] = 0.0;
+
+  for (int k0 = 0; k0 < M; k0 += KC) {
+    {  // x tile: 64 tokens x 32 k = 256 groups of 8 consecutive k
+      const int tok = tid >> 2, kq = (tid & 3) * 8;
+      float f[8];
+      load8<BF16>(x, (t0 + tok) * (int64_t)M + k0 + kq, (t0 + tok < S) && (k0 + kq < M), f);
+#pragma unroll
+      for (int i = 0; i < 8; ++i) xs[kq + i][tok] = f[i];
+    }
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {  // Wg tile: 32 k x 64 experts
+      const int c = tid + i * 256;
+      const int kk = c >> 6, ee = c & 63;
+      wsm[kk][ee] = (k0 + kk < M && e0 + ee < E) ? Wg[(int64_t)(k0 + kk) * E + e0 + ee] : 0.f;
+    }
+    __syncthreads();
+#pragma unroll 8
+    for (int kk = 0; kk < KC; ++kk) {
+      const float4 xv = *reinterpret_cast<const float4*>(&xs[kk][ty * 4]);
+      const float4 wv = *reinterpret_cast<const float4*>(&wsm[kk][tx * 4]);
+      const double xd[4] = {(double)xv.x, (double)xv.y, (double)xv.z, (double)xv.w};
+      const double wd[4] = {(double)wv.x, (double)wv.y, (double)wv.z, (double)wv.w};
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) acc[i][j] = fma(xd[i], wd[j], acc[i][j]);
+    }
+    __syncthreads();
+  }
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const int64_t t = t0 + ty * 4 + i;
+    if (t >= S) continue;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const int e = e0 + tx * 4 + j;
+      if (e < E) logits[t * E + e] = (float)(acc[i][j] + (bias ? (double)bias[e] : 0.0));
+    }
+  }
+}
+
+struct Cand {
+  float v;
+  int e;  // INT_MAX = no candidate
+};
+__device__ __forceinline__ Cand better(Cand a, Cand b) {
+  if (b.e == 0x7fffffff) return a;
+  if (a.e == 0x7fffffff) return b;
+  if (b.v > a.v || (b.v == a.v && b.e < a.e)) return b;
+  return a;
+}
+
+// W lanes per token (W = pow2, W*EPL >= E).  Lane r of a group holds experts r, r+W, ...
+template <int W, int EPL>
+__global__ __launch_bounds__(GATE_TB) void gate_topk(const float* __restrict__ logits, int64_t S, int E, int k,
+                                                      int norm_topk, int32_t* __restrict__ idx, float* __restrict__ w,
+                                                      int32_t* __restrict__ blockhist) {
+  __shared__ int hist[MOE_MAX_K * MOE_MAX_E];
+  const int tid = threadIdx.x;
+  for (int i = tid; i < k * E; i += GATE_TB) hist[i] = 0;
+  __syncthreads();
+  const int r = tid % W;
+  const int64_t tb0 = (int64_t)blockIdx.x * GATE_TB;
+  constexpr int TPP = GATE_TB / W;  // tokens per pass
+  for (int pass = 0; pass < W; ++pass) {
+    const int64_t t = tb0 + pass * TPP + tid / W;
+    const bool live = t < S;
+    float v[EPL];
+    unsigned taken = 0;
+#pragma unroll
+    for (int i = 0; i < EPL; ++i) {
+      const int e = r + i * W;
+      v[i] = (live && e < E) ? logits[t * E + e] : 0.f;
+      if (!(live && e < E)) taken |= 1u << i;
+    }
+    float selv[MOE_MAX_K];
+    int sele[MOE_MAX_K];
+#pragma unroll
+    for (int j = 0; j < MOE_MAX_K; ++j) {
+      selv[j] = 0.f; sele[j] = 0;
+      if (j < k) {
+        Cand c{0.f, 0x7fffffff};
+#pragma unroll
+        for (int i = 0; i < EPL; ++i)
+          if (!(taken & (1u << i))) c = better(c, Cand{v[i], r + i * W});
+#pragma unroll
+        for (int m = 1; m < W; m <<= 1) {
+          Cand o;
+          o.v = __shfl_xor(c.v, m, 64);
+          o.e = __shfl_xor(c.e, m, 64);
+          c = better(c, o);
+        }
+        selv[j] = c.v; sele[j] = c.e;
+#pragma unroll
+        for (int i = 0; i < EPL; ++i)
+          if (c.e == r + i * W) taken |= 1u << i;
+      }
+    }
+    // weights: exp(l - max) over the selected k, or over all experts
+    const float mx = selv[0];
+    float den = 0.f;
+    if (norm_topk) {
+#pragma unroll
+      for (int j = 0; j < MOE_MAX_K; ++j)
+        if (j < k) den += expf(selv[j] - mx);
+    } else {
+      float part = 0.f;
+#pragma unroll
+      for (int i = 0; i < EPL; ++i) {
+        const int e = r + i * W;
+        if (live && e < E) part += expf(v[i] - mx);
+      }
+#pragma unroll
+      for (int m = 1; m < W; m <<= 1) part += __shfl_xor(part, m, 64);
+      den = part;
+    }
+    if (live && r < k) {
+      float lv = 0.f; int le = 0;
+#pragma unroll
+      for (int j = 0; j < MOE_MAX_K; ++j)
+        if (j == r) { lv = selv[j]; le = sele[j]; }
+      idx[t * k + r] = le;
+      w[t * k + r] = expf(lv - mx) / den;
+      atomicAdd(&hist[r * E + le], 1);
+    }
+  }
+  __syncthreads();
+  // stored [choice][expert][block] so the scan reads one (choice, expert) row contiguously
+  for (int i = tid; i < k * E; i += GATE_TB) blockhist[(int64_t)i * gridDim.x + blockIdx.x] = hist[i];
+}
+
+// blockhist[j][e][b] -> blockbase[j][e][b] = queue position of the first (token, choice j) of
+// token block b at expert e.  Choice-major: all choice-0 demand of e precedes choice 1, ...
+// One wave per expert; 64 blocks are scanned per step with a shuffle prefix sum.
+__global__ __launch_bounds__(256) void gate_scan(const int32_t* __restrict__ blockhist, int nblk, int E, int k,
+                                                 int32_t* __restrict__ blockbase, int32_t* __restrict__ counts) {
+  const int lane = threadIdx.x & 63;
+  const int e = blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6);
+  if (e >= E) return;
+  int run = 0;
+  for (int j = 0; j < k; ++j) {
+    const int64_t row = ((int64_t)j * E + e) * nblk;
+    for (int b0 = 0; b0 < nblk; b0 += 64) {
+      const int b = b0 + lane;
+      const int h = b < nblk ? blockhist[row + b] : 0;
+      int incl = h;
+#pragma unroll
+      for (int d = 1; d < 64; d <<= 1) {
+        const int o = __shfl_up(incl, d, 64);
+        if (lane >= d) incl += o;
+      }
+      if (b < nblk) blockbase[row + b] = run + incl - h;
+      run += __shfl(incl, 63, 64);
+    }
+  }
+  if (lane == 0) counts[e] = run;
+}
+
+__global__ __launch_bounds__(GATE_TB) void gate_slots(const int32_t* __restrict__ idx, const int32_t* __restrict__ blockbase,
+                                                       const int32_t* __restrict__ counts, int64_t S, int E, int k,
+                                                       int64_t C, int32_t* __restrict__ slot, int32_t* __restrict__ inv) {
+  __shared__ int wavecnt[GATE_TB / 64][MOE_MAX_E];
+  const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+  const int64_t t = (int64_t)blockIdx.x * GATE_TB + tid;
+  const bool live = t < S;
+  for (int j = 0; j < k; ++j) {
+    for (int i = tid; i < (GATE_TB / 64) * MOE_MAX_E; i += GATE_TB) (&wavecnt[0][0])[i] = 0;
+    __syncthreads();
+    const int e = live ? idx[t * k + j] : -1;
+    int rank = 0;
+    unsigned long long todo = __ballot(live);
+    while (todo) {
+      const int leader = __ffsll((long long)todo) - 1;
+      const int e0 = __shfl(e, leader, 64);
+      const unsigned long long same = __ballot(live && e == e0);
+      if (e == e0) {
+        rank = __popcll(same & ((1ull << lane) - 1ull));
+        if (lane == leader) wavecnt[wv][e0] = __popcll(same);
+      }
+      todo &= ~same;
+    }
+    __syncthreads();
+    if (live) {
+      int pos = blockbase[((int64_t)j * E + e) * gridDim.x + blockIdx.x] + rank;
+      for (int q = 0; q < wv; ++q) pos += wavecnt[q][e];
+      const bool keep = pos < C;
+      slot[t * k + j] = keep ? pos : -1;
+      if (keep) inv[(int64_t)e * C + pos] = (int32_t)(t * k + j);
+    }
+    __syncthreads();
+  }
+  // empty tail of every expert's block: slots [min(counts[e], C), C)
+  const int64_t total = (int64_t)E * C;
+  for (int64_t i = (int64_t)blockIdx.x * GATE_TB + tid; i < total; i += (int64_t)gridDim.x * GATE_TB) {
+    const int e = (int)(i / C);
+    const int64_t c = i - (int64_t)e * C;
+    if (c >= counts[e]) inv[i] = -1;
+  }
+}
+
+template <int W, int EPL>
+void launch_topk(const float* logits, int64_t S, int E, int k, int norm, int32_t* idx, float* w, int32_t* bh,
+                 int nblk, hipStream_t st) {
+  hipLaunchKernelGGL((gate_topk<W, EPL>), dim3(nblk), dim3(GATE_TB), 0, st, logits, S, E, k, norm, idx, w, bh);
+}
+
+}  // namespace
+
+extern "C" size_t moe_gate_workspace_bytes(int64_t S, int E, int k) {
+  if (S < 1 || E < 1 || k < 1) return 0;
+  const int64_t nblk = (S + GATE_TB - 1) / GATE_TB;
+  return moe::align_up((size_t)nblk * k * E * sizeof(int32_t), 256) * 2;
+}
+
+extern "C" int moe_gate_topk(const void* x, int x_dtype, const float* Wg, const float* gate_bias,
+                             int64_t S_total, int M, int E, int k, int64_t C, int mp_idx, int n_mp, int norm_topk,
+                             float* logits, int32_t* idx, int32_t* slot, float* w, int32_t* inv, int32_t* counts,
+                             void* ws, size_t ws_bytes, void* stream) {
+  MOE_REQUIRE(n_mp >= 1 && mp_idx >= 0 && mp_idx < n_mp, MOE_EINVAL);
+  MOE_REQUIRE(S_total >= 1 && S_total % n_mp == 0, MOE_EINVAL);
+  const int64_t S = S_total / n_mp;
+  if (int rc = moe::common_shape_check(S, x ? M : 8, E, k, C)) return rc;
+  MOE_REQUIRE(norm_topk >= -1 && norm_topk <= 1, MOE_EINVAL);
+  if (x) {
+    MOE_REQUIRE(x_dtype == MOE_F32 || x_dtype == MOE_BF16, MOE_EINVAL);
+    MOE_REQUIRE_PTR(x);
+    MOE_REQUIRE_PTR(Wg);
+  }
+  MOE_OPTIONAL_PTR(gate_bias);
+  MOE_REQUIRE_PTR(logits); MOE_REQUIRE_PTR(idx); MOE_REQUIRE_PTR(slot); MOE_REQUIRE_PTR(w);
+  MOE_REQUIRE_PTR(inv); MOE_REQUIRE_PTR(counts);
+  const size_t need = moe_gate_workspace_bytes(S, E, k);
+  MOE_REQUIRE(ws != nullptr && ws_bytes >= need, MOE_EWORKSPACE);
+  MOE_REQUIRE(moe::aligned16(ws), MOE_EALIGN);
+  const int norm = norm_topk < 0 ? (k >= 2 ? 1 : 0) : norm_topk;
+  hipStream_t st = (hipStream_t)stream;
+  const int nblk = (int)((S + GATE_TB - 1) / GATE_TB);
+  int32_t* blockhist = (int32_t*)ws;
+  int32_t* blockbase = (int32_t*)((char*)ws + need / 2);
+
+  if (x) {
+    const bool bf = x_dtype == MOE_BF16;
+    const size_t esz = bf ? 2 : 4;
+    const void* xs = (const char*)x + (size_t)mp_idx * S * M * esz;
+    if (E <= 16) {
+      const int EC = E <= 4 ? 4 : (E <= 8 ? 8 : 16);
+      const int T = 64 / EC;
+      const int64_t waves = (S + T - 1) / T;
+      const dim3 grid((unsigned)waves), block(64);
+      const bool full = (E == EC);
+#define LAUNCH_SMALL2(ec, b16, fl) \
+  hipLaunchKernelGGL((gate_logits_small_e<ec, b16, fl>), grid, block, 0, st, xs, Wg, gate_bias, logits, S, M, E)
+#define LAUNCH_SMALL(ec) do { \
+    if (bf) { if (full) LAUNCH_SMALL2(ec, true, true); else LAUNCH_SMALL2(ec, true, false); } \
+    else { if (full) LAUNCH_SMALL2(ec, false, true); else LAUNCH_SMALL2(ec, false, false); } } while (0)
+      if (EC == 4) LAUNCH_SMALL(4); else if (EC == 8) LAUNCH_SMALL(8); else LAUNCH_SMALL(16);
+#undef LAUNCH_SMALL
+#undef LAUNCH_SMALL2
+    } else {
+      const dim3 grid((unsigned)((S + 63) / 64), (unsigned)((E + 63) / 64)), block(256);
+      if (bf) hipLaunchKernelGGL((gate_logits_tiled<true>), grid, block, 0, st, xs, Wg, gate_bias, logits, S, M, E);
+      else hipLaunchKernelGGL((gate_logits_tiled<false>), grid, block, 0, st, xs, Wg, gate_bias, logits, S, M, E);
+    }
+  }
+  if (E <= 1) launch_topk<1, 1>(logits, S, E, k, norm, idx, w, blockhist, nblk, st);
+  else if (E <= 2) launch_topk<2, 1>(logits, S, E, k, norm, idx, w, blockhist, nblk, st);
+  else if (E <= 4) launch_topk<4, 1>(logits, S, E, k, norm, idx, w, blockhist, nblk, st);
+  else if (E <= 8) launch_topk<8, 1>(logits, S, E, k, norm, idx, w, blockhist, nblk, st);
+  else if (E <= 16) launch_topk<16, 1>(logits, S, E, k, norm, idx, w, blockhist, nblk, st);
+  else if (E <= 32) launch_topk<32, 1>(logits, S, E, k, norm, idx, w, blockhist, nblk, st);
+  else if (E <= 64) launch_topk<64, 1>(logits, S, E, k, norm, idx, w, blockhist, nblk, st);
+  else if (E <= 128) launch_topk<64, 2>(logits, S, E, k, norm, idx, w, blockhist, nblk, st);
+  else launch_topk<64, 4>(logits, S, E, k, norm, idx, w, blockhist, nblk, st);
+  hipLaunchKernelGGL(gate_scan, dim3((E + 3) / 4), dim3(256), 0, st, blockhist, nblk, E, k, blockbase, counts);
+  hipLaunchKernelGGL(gate_slots, dim3(nblk), dim3(GATE_TB), 0, st, idx, blockbase, counts, S, E, k, C, slot, inv);
+  return moe::check_launch();
+}

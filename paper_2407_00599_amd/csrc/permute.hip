@@ -1,0 +1,204 @@
+// Dispatch and combine of the MoE layer (Section II-A: G[i,:,:] holds the tokens of expert i;
+// the expert outputs are combined back to token order) and the local sum of the N_ESP
+// partial results that return through the EP&ESP-AlltoAll (Section III-C).
+//
+// All three kernels are row movers bound by HBM bandwidth.  They run in gather form: every
+// output row is produced by exactly one wave, reading its source rows through the slot
+// maps, so there are no atomics and no prior memset; 16-byte accesses per lane.
+#include "common.h"
+
+namespace {
+
+using namespace moe;
+
+// 8 consecutive elements as fp32
+template <bool BF16>
+__device__ __forceinline__ void ld8(const void* base, int64_t off, float* f) {
+  if (BF16) {
+    unpack_bf16x8(*reinterpret_cast<const uint4*>(reinterpret_cast<const bf16_t*>(base) + off), f);
+  } else {
+    const float4* p = reinterpret_cast<const float4*>(reinterpret_cast<const float*>(base) + off);
+    const float4 a = p[0], b = p[1];
+    f[0] = a.x; f[1] = a.y; f[2] = a.z; f[3] = a.w; f[4] = b.x; f[5] = b.y; f[6] = b.z; f[7] = b.w;
+  }
+}
+template <bool BF16>
+__device__ __forceinline__ void st8(void* base, int64_t off, const float* f) {
+  if (BF16) {
+    *reinterpret_cast<uint4*>(reinterpret_cast<bf16_t*>(base) + off) = pack_bf16x8(f);
+  } else {
+    float4* p = reinterpret_cast<float4*>(reinterpret_cast<float*>(base) + off);
+    p[0] = make_float4(f[0], f[1], f[2], f[3]);
+    p[1] = make_float4(f[4], f[5], f[6], f[7]);
+  }
+}
+
+// buf[row,:] = (w?) * x[inv[row]/k, :]  or zeros.  One wave per output row.
+template <bool BF16>
+__global__ __launch_bounds__(256) void dispatch_rows(const void* __restrict__ x, const int32_t* __restrict__ inv,
+                                                     const float* __restrict__ w, void* __restrict__ buf,
+                                                     int64_t rows, int M, int k) {
+  const int lane = threadIdx.x & 63;
+  const int64_t row = (int64_t)blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6);
+  if (row >= rows) return;
+  const int a = inv[row];
+  const int64_t dst = row * (int64_t)M;
+  if (a < 0) {
+    const float z[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+    for (int m = lane * 8; m < M; m += 512) st8<BF16>(buf, dst + m, z);
+    return;
+  }
+  const int64_t src = (int64_t)(a / k) * M;
+  if (w == nullptr) {
+    if (BF16) {
+      for (int m = lane * 8; m < M; m += 512)
+        *reinterpret_cast<uint4*>(reinterpret_cast<bf16_t*>(buf) + dst + m) =
+            *reinterpret_cast<const uint4*>(reinterpret_cast<const bf16_t*>(x) + src + m);
+    } else {
+      for (int m = lane * 4; m < M; m += 256)
+        *reinterpret_cast<float4*>(reinterpret_cast<float*>(buf) + dst + m) =
+            *reinterpret_cast<const float4*>(reinterpret_cast<const float*>(x) + src + m);
+    }
+  } else {
+    const float s = w[a];
+    for (int m = lane * 8; m < M; m += 512) {
+      float f[8];
+      ld8<BF16>(x, src + m, f);
+#pragma unroll
+      for (int i = 0; i < 8; ++i) f[i] *= s;
+      st8<BF16>(buf, dst + m, f);
+    }
+  }
+}
+
+// y[t,:] = sum_j w[t,j] * sum_p Yret[p, idx[t,j], slot[t,j], :].  One wave per token.
+template <bool BF16>
+__global__ __launch_bounds__(256) void combine_rows(const void* __restrict__ Yret, const int32_t* __restrict__ idx,
+                                                    const int32_t* __restrict__ slot, const float* __restrict__ w,
+                                                    void* __restrict__ y, int64_t S, int M, int k, int64_t C,
+                                                    int n_part, int64_t part_stride) {
+  const int lane = threadIdx.x & 63;
+  const int64_t t = (int64_t)blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6);
+  if (t >= S) return;
+  int64_t src[MOE_MAX_K];
+  float wt[MOE_MAX_K];
+#pragma unroll
+  for (int j = 0; j < MOE_MAX_K; ++j) {
+    src[j] = -1; wt[j] = 0.f;
+    if (j < k) {
+      const int c = slot[t * k + j];
+      if (c >= 0) {
+        src[j] = ((int64_t)idx[t * k + j] * C + c) * M;
+        wt[j] = w ? w[t * k + j] : 1.f;
+      }
+    }
+  }
+  for (int m = lane * 8; m < M; m += 512) {
+    float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int j = 0; j < MOE_MAX_K; ++j) {
+      if (j < k && src[j] >= 0) {
+        float r[8];
+        ld8<BF16>(Yret, src[j] + m, r);
+        for (int p = 1; p < n_part; ++p) {
+          float q[8];
+          ld8<BF16>(Yret, src[j] + m + p * part_stride, q);
+#pragma unroll
+          for (int i = 0; i < 8; ++i) r[i] += q[i];
+        }
+#pragma unroll
+        for (int i = 0; i < 8; ++i) acc[i] = fmaf(wt[j], r[i], acc[i]);
+      }
+    }
+    st8<BF16>(y, t * (int64_t)M + m, acc);
+  }
+}
+
+// dw[t,j] = <dy[t,:], sum_p Yret[p, idx, slot, :]>, 0 for dropped choices.  One wave per token.
+template <bool BF16>
+__global__ __launch_bounds__(256) void combine_dw(const void* __restrict__ dy, const void* __restrict__ Yret,
+                                                  const int32_t* __restrict__ idx, const int32_t* __restrict__ slot,
+                                                  float* __restrict__ dw, int64_t S, int M, int k, int64_t C,
+                                                  int n_part, int64_t part_stride) {
+  const int lane = threadIdx.x & 63;
+  const int64_t t = (int64_t)blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6);
+  if (t >= S) return;
+  for (int j = 0; j < k; ++j) {
+    const int c = slot[t * k + j];
+    float dot = 0.f;
+    if (c >= 0) {
+      const int64_t src = ((int64_t)idx[t * k + j] * C + c) * M;
+      for (int m = lane * 8; m < M; m += 512) {
+        float g[8], r[8];
+        ld8<BF16>(dy, t * (int64_t)M + m, g);
+        ld8<BF16>(Yret, src + m, r);
+        for (int p = 1; p < n_part; ++p) {
+          float q[8];
+          ld8<BF16>(Yret, src + m + p * part_stride, q);
+#pragma unroll
+          for (int i = 0; i < 8; ++i) r[i] += q[i];
+        }
+#pragma unroll
+        for (int i = 0; i < 8; ++i) dot = fmaf(g[i], r[i], dot);
+      }
+#pragma unroll
+      for (int o = 32; o >= 1; o >>= 1) dot += __shfl_xor(dot, o, 64);
+    }
+    if (lane == 0) dw[t * k + j] = dot;
+  }
+}
+
+}  // namespace
+
+extern "C" int moe_dispatch(const void* x, int dtype, int64_t S, int M, int E, int k, int64_t C,
+                            const int32_t* inv, const float* w, void* buf, void* stream) {
+  if (int rc = moe::common_shape_check(S, M, E, k, C)) return rc;
+  MOE_REQUIRE(dtype == MOE_F32 || dtype == MOE_BF16, MOE_EINVAL);
+  MOE_REQUIRE_PTR(x); MOE_REQUIRE_PTR(inv); MOE_REQUIRE_PTR(buf);
+  MOE_OPTIONAL_PTR(w);
+  const int64_t rows = (int64_t)E * C;
+  const dim3 grid((unsigned)((rows + 3) / 4)), block(256);
+  hipStream_t st = (hipStream_t)stream;
+  if (dtype == MOE_BF16) hipLaunchKernelGGL(dispatch_rows<true>, grid, block, 0, st, x, inv, w, buf, rows, M, k);
+  else hipLaunchKernelGGL(dispatch_rows<false>, grid, block, 0, st, x, inv, w, buf, rows, M, k);
+  return moe::check_launch();
+}
+
+extern "C" int moe_combine_fwd(const void* Yret, int dtype, int n_part, int64_t S, int M, int E, int k, int64_t C,
+                               const int32_t* idx, const int32_t* slot, const float* w, void* y, void* stream) {
+  if (int rc = moe::common_shape_check(S, M, E, k, C)) return rc;
+  MOE_REQUIRE(dtype == MOE_F32 || dtype == MOE_BF16, MOE_EINVAL);
+  MOE_REQUIRE(n_part >= 1 && n_part <= 64, MOE_EINVAL);
+  MOE_REQUIRE_PTR(Yret); MOE_REQUIRE_PTR(idx); MOE_REQUIRE_PTR(slot); MOE_REQUIRE_PTR(y);
+  MOE_OPTIONAL_PTR(w);
+  const dim3 grid((unsigned)((S + 3) / 4)), block(256);
+  const int64_t ps = (int64_t)E * C * M;
+  hipStream_t st = (hipStream_t)stream;
+  if (dtype == MOE_BF16)
+    hipLaunchKernelGGL(combine_rows<true>, grid, block, 0, st, Yret, idx, slot, w, y, S, M, k, C, n_part, ps);
+  else
+    hipLaunchKernelGGL(combine_rows<false>, grid, block, 0, st, Yret, idx, slot, w, y, S, M, k, C, n_part, ps);
+  return moe::check_launch();
+}
+
+extern "C" int moe_combine_bwd(const void* dy, const void* Yret, int dtype, int n_part, int64_t S, int M, int E,
+                               int k, int64_t C, const int32_t* idx, const int32_t* slot, const int32_t* inv,
+                               const float* w, void* dYret, float* dw, void* stream) {
+  if (int rc = moe::common_shape_check(S, M, E, k, C)) return rc;
+  MOE_REQUIRE(dtype == MOE_F32 || dtype == MOE_BF16, MOE_EINVAL);
+  MOE_REQUIRE(n_part >= 1 && n_part <= 64, MOE_EINVAL);
+  MOE_REQUIRE_PTR(dy); MOE_REQUIRE_PTR(Yret); MOE_REQUIRE_PTR(idx); MOE_REQUIRE_PTR(slot); MOE_REQUIRE_PTR(inv);
+  MOE_REQUIRE_PTR(w); MOE_REQUIRE_PTR(dYret); MOE_REQUIRE_PTR(dw);
+  hipStream_t st = (hipStream_t)stream;
+  const int64_t rows = (int64_t)E * C;
+  const int64_t ps = rows * M;
+  const dim3 block(256), grid_r((unsigned)((rows + 3) / 4)), grid_t((unsigned)((S + 3) / 4));
+  if (dtype == MOE_BF16) {
+    hipLaunchKernelGGL(dispatch_rows<true>, grid_r, block, 0, st, dy, inv, w, dYret, rows, M, k);
+    hipLaunchKernelGGL(combine_dw<true>, grid_t, block, 0, st, dy, Yret, idx, slot, dw, S, M, k, C, n_part, ps);
+  } else {
+    hipLaunchKernelGGL(dispatch_rows<false>, grid_r, block, 0, st, dy, inv, w, dYret, rows, M, k);
+    hipLaunchKernelGGL(combine_dw<false>, grid_t, block, 0, st, dy, Yret, idx, slot, dw, S, M, k, C, n_part, ps);
+  }
+  return moe::check_launch();
+}

@@ -1,0 +1,73 @@
+"""Call sequence of one rank's MoE layer over the C ABI, with preallocated device buffers.
+
+`MoERankLayer` strings the entry points together the way a training step would between the
+collectives of Section III (gate -> dispatch -> [AlltoAll] -> expert FFN -> [AlltoAll] ->
+combine, and the mirror image backward).  With all E experts local and the N_ESP shards run
+one after the other on the same GPU it evaluates the whole layer ("closed world"), which is
+what the parity tests compare with the CPU checker.  Nothing is computed here: every step is
+a library call; torch only owns the memory.
+"""
+from __future__ import annotations
+
+import torch
+
+from . import api
+
+
+class MoERankLayer:
+    def __init__(self, S_total, M, H, E, k, f, dtype=torch.bfloat16, n_mp=1, mp_idx=0, n_esp=1,
+                 norm_topk=-1, device="cuda:0"):
+        self.S_total, self.M, self.H, self.E, self.k, self.f = S_total, M, H, E, k, f
+        self.n_mp, self.mp_idx, self.n_esp, self.norm_topk = n_mp, mp_idx, n_esp, norm_topk
+        self.dtype, self.dev = dtype, torch.device(device)
+        self.S = S = S_total // n_mp
+        self.C = C = api.moe_capacity(S, E, k, f)
+        self.Hl = Hl = H // n_esp
+        self.dt = api.MOE_BF16 if dtype == torch.bfloat16 else api.MOE_F32
+        dev = self.dev
+        i32, f32 = torch.int32, torch.float32
+        e = lambda *shape, dt=dtype: torch.empty(shape, dtype=dt, device=dev)
+        self.logits = e(S, E, dt=f32); self.idx = e(S, k, dt=i32); self.slot = e(S, k, dt=i32)
+        self.w = e(S, k, dt=f32); self.inv = e(E, C, dt=i32); self.counts = e(E, dt=i32)
+        self.buf = e(E, C, M)
+        self.Z = e(n_esp, E, C, Hl)
+        self.Yret = e(n_esp, E, C, M)
+        self.y = e(S, M)
+        # backward
+        self.dYret = e(E, C, M); self.dw = e(S, k, dt=f32)
+        self.dbuf = e(n_esp, E, C, M)
+        self.dW1 = e(E, M, H); self.dW2 = e(E, H, M)
+        self.dx = e(S, M); self.dlogits = e(S, E, dt=f32); self.dWg = e(M, E, dt=f32); self.dbias = e(E, dt=f32)
+        nbytes = max(api.moe_gate_workspace_bytes(S, E, k),
+                     api.moe_ffn_workspace_bytes(self.dt, 1, E, C, M, H, n_esp, 1),
+                     api.moe_gate_bwd_workspace_bytes(S, M, E), 256)
+        self.ws = torch.empty(nbytes, dtype=torch.uint8, device=dev)
+
+    def gate(self, x_full, Wg, bias):
+        api.moe_gate_topk(x_full, Wg, bias, self.S_total, self.M, self.E, self.k, self.C, self.mp_idx, self.n_mp,
+                          self.norm_topk, self.logits, self.idx, self.slot, self.w, self.inv, self.counts, self.ws)
+
+    def forward(self, x_full, Wg, bias, W1, W2):
+        """x_full [S_total, M]; returns y [S, M] for the rank's token block."""
+        S, M, E, k, C, H = self.S, self.M, self.E, self.k, self.C, self.H
+        self.x = x_full[self.mp_idx * S:(self.mp_idx + 1) * S]
+        self.Wg, self.W1, self.W2 = Wg, W1, W2
+        self.gate(x_full, Wg, bias)
+        api.moe_dispatch(self.x, S, M, E, k, C, self.inv, None, self.buf)
+        for j in range(self.n_esp):           # the N_ESP shards of every expert, one after the other
+            api.moe_expert_ffn_fwd(self.buf, W1, W2, 1, E, C, M, H, j, self.n_esp, self.Z[j], self.Yret[j], self.ws)
+        api.moe_combine_fwd(self.Yret, self.n_esp, S, M, E, k, C, self.idx, self.slot, self.w, self.y)
+        return self.y
+
+    def backward(self, dy):
+        S, M, E, k, C, H = self.S, self.M, self.E, self.k, self.C, self.H
+        api.moe_combine_bwd(dy, self.Yret, self.n_esp, S, M, E, k, C, self.idx, self.slot, self.inv, self.w,
+                            self.dYret, self.dw)
+        for j in range(self.n_esp):
+            api.moe_expert_ffn_bwd(self.dYret, self.buf, self.Z[j], self.W1, self.W2, 1, E, C, M, H, j, self.n_esp,
+                                   self.dbuf[j], self.dW1, self.dW2, self.ws)
+        # backward of dispatch = unweighted combine of the (n_esp partial) input gradients
+        api.moe_combine_fwd(self.dbuf, self.n_esp, S, M, E, k, C, self.idx, self.slot, None, self.dx)
+        api.moe_gate_bwd(self.dw, self.w, self.idx, self.logits, self.x, self.Wg, S, M, E, k, self.norm_topk,
+                         self.dlogits, self.dWg, self.dbias, self.dx, 1, self.ws)
+        return self.dx
