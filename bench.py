@@ -1,0 +1,158 @@
+#!/usr/bin/env python3
+"""Benchmark of one rank's MoE-layer step (gate, dispatch, expert FFN, combine; fwd+bwd) on ONE MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config layer_bf16] [--no-cpu-baseline]
+
+A step is one pass of the whole hot path over one batch of seeded synthetic input that is
+already resident in HBM.  Prints ONE JSON line: tokens/s of the layer fwd+bwd, the roofline of
+the dominant kernel family (the grouped bf16 MFMA GEMMs of the expert FFN: flops per launch /
+mean launch time, timed with HIP events on the launch stream inside the timed steps) and the
+CPU checker timed on the host cores on the same workload.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+MFMA_BF16_PEAK_TFLOPS = 2500.0   # MI355X dense bf16 matrix peak
+HBM_PEAK_GBS = 8000.0
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=30)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--config", default="layer_bf16", help="workload name from synth.CONFIGS")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--tile", type=int, default=0, help="FFN GEMM tile: 0 auto, 1 = 128x128, 2 = 256x256")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py measures one rank on one GPU: this build has no inter-GPU collectives, "
+              "run it with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    from paper_2407_00599_amd import api, synth
+    from paper_2407_00599_amd.layer import MoERankShape
+
+    api.lib()
+    if not torch.cuda.is_available():
+        print("bench.py needs a GPU (no CPU fallback exists)", file=sys.stderr)
+        sys.exit(2)
+    dev = "cuda:0"
+    torch.cuda.set_device(0)
+    api.moe_ffn_set_tile(args.tile)
+    cfg = synth.CONFIGS[args.config]
+    tdt = torch.float32 if cfg.dtype == "f32" else torch.bfloat16
+    norm = 0 if cfg.k == 1 else 1
+
+    L = MoERankShape(cfg.S_total, cfg.M, cfg.H, cfg.E, cfg.k, cfg.f, dtype=tdt, n_mp=cfg.n_mp, mp_idx=cfg.mp_idx,
+                     n_ep=cfg.n_ep, n_esp=cfg.n_esp, esp_idx=cfg.esp_idx, norm_topk=norm, device=dev)
+
+    def dev_t(st):
+        if isinstance(st, synth.Stored):
+            if st.bits is None:
+                return torch.from_numpy(st.val).to(dev)
+            return torch.from_numpy(st.bits.view(np.int16)).to(dev).view(torch.bfloat16)
+        return None if st is None else torch.from_numpy(np.ascontiguousarray(st)).to(dev)
+
+    host = {}
+    small = cfg.cfg_id <= 3          # host-generated inputs, shared with the CPU baseline
+    if small:
+        host["x"] = synth.tokens(cfg); host["Wg"] = synth.gate_weight(cfg); host["bias"] = synth.gate_bias(cfg)
+        host["W1"], host["W2"] = synth.expert_weights(cfg, L.G); host["dy"] = synth.upstream_grad(cfg)
+        x, Wg, bias = dev_t(host["x"]), dev_t(host["Wg"]), dev_t(host["bias"])
+        W1, W2, dy = dev_t(host["W1"]), dev_t(host["W2"]), dev_t(host["dy"])
+    else:                            # large shapes: same distributions, drawn on the device
+        gen = torch.Generator(device=dev); gen.manual_seed(synth.BASE_SEED + cfg.cfg_id)
+        rn = lambda *s, sig=1.0, dt=tdt: (torch.randn(*s, generator=gen, device=dev, dtype=torch.float32) * sig).to(dt)
+        x = rn(cfg.S_total, cfg.M, sig=cfg.sigma_x); Wg = rn(cfg.M, cfg.E, sig=cfg.sigma_w, dt=torch.float32)
+        b = synth.gate_bias(cfg); bias = dev_t(b)
+        W1 = torch.empty(L.G, cfg.M, cfg.H, dtype=tdt, device=dev); W2 = torch.empty(L.G, cfg.H, cfg.M, dtype=tdt, device=dev)
+        for g in range(L.G):
+            W1[g] = rn(cfg.M, cfg.H, sig=cfg.sigma_w); W2[g] = rn(cfg.H, cfg.M, sig=cfg.sigma_w)
+        dy = rn(L.S, cfg.M)
+    L.bind(x, Wg, bias, W1, W2, dy)
+    if not L.closed:
+        # stand-ins for what the two EP&ESP-AlltoAlls would deliver (rows ~N(0,1), 80 % occupied)
+        gen = torch.Generator(device=dev); gen.manual_seed(synth.BASE_SEED + 77)
+        for t in (L.Xrecv, L.dYrecv):
+            t.copy_(torch.randn(t.shape, generator=gen, device=dev, dtype=torch.float32).to(tdt))
+            t[:, :, int(0.8 * L.C):, :] = 0
+        for t in (L.Yret, L.dbuf):
+            t.copy_((torch.randn(t.shape, generator=gen, device=dev, dtype=torch.float32) * 0.5).to(tdt))
+
+    names = MoERankShape.STEPS
+    for _ in range(args.warmup):
+        L.step()
+    torch.cuda.synchronize()
+
+    K = args.steps
+    ev = [[torch.cuda.Event(enable_timing=True) for _ in range(len(names) + 1)] for _ in range(K)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for s in range(K):
+        ev[s][0].record()
+        for i, n in enumerate(names):
+            getattr(L, n)()
+            ev[s][i + 1].record()
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms_per_step = (t1 - t0) * 1e3 / K
+    per_call = {n: sum(ev[s][i].elapsed_time(ev[s][i + 1]) for s in range(K)) / K for i, n in enumerate(names)}
+
+    # dominant kernel family: the six grouped GEMM launches of the expert FFN (2 fwd, 4 bwd),
+    # each 2 * rows * M * H_l flops over the capacity-padded rows of the rank
+    rows = L.n_src * L.G * L.C
+    flops_per_launch = 2.0 * rows * cfg.M * L.Hl
+    gemm_ms = (per_call["ffn_fwd"] + per_call["ffn_bwd"]) / 6.0
+    achieved = flops_per_launch / (gemm_ms * 1e-3) / 1e12
+    roofline = {"bound": "mfma", "achieved": round(achieved, 2), "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
+                "frac": round(achieved / MFMA_BF16_PEAK_TFLOPS, 4), "traffic": None,
+                "kernel": "ffn_gemm_bf16 (6 launches per step)", "launch_ms": round(gemm_ms, 4),
+                "flops_per_launch": flops_per_launch}
+    if cfg.dtype == "f32":
+        roofline.update({"bound": "alu", "peak": 78.6, "frac": round(achieved / 78.6, 5),
+                         "kernel": "ffn_gemm_f32 (6 launches per step)"})
+
+    cpu = None
+    if small and not args.no_cpu_baseline and L.closed:
+        from oracle import moe_oracle as O
+        try:
+            from threadpoolctl import threadpool_info
+            cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+        except Exception:
+            cores = os.cpu_count()
+        xs = host["x"].val[O.mp_slice(cfg.S_total, cfg.mp_idx, cfg.n_mp)]
+        passes, tcpu = 0, 0.0
+        while passes < 5 and tcpu < 10.0:
+            c0 = time.perf_counter()
+            r = O.layer_fwd(xs, host["Wg"], host["bias"], host["W1"].val, host["W2"].val, cfg.k, cfg.f, bool(norm), 1)
+            O.layer_bwd(r, host["dy"].val, xs, host["Wg"], host["W1"].val, host["W2"].val, cfg.k, bool(norm), 1)
+            tcpu += time.perf_counter() - c0
+            passes += 1
+        cpu = {"value": round(L.S * passes / tcpu, 1), "unit": "tokens/s", "cores": int(cores), "kind": "oracle",
+               "sample": f"{passes} full fwd+bwd passes of the same {cfg.name} workload (numpy float64)"}
+
+    out = {
+        "metric": "MoE-layer fwd+bwd tokens/s (1 GPU)", "value": round(L.S / (ms_per_step * 1e-3), 1), "unit": "tokens/s",
+        "n_gpus": 1, "steps": K, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16" if cfg.dtype == "bf16" else "f32", "data": "synthetic",
+        "config": {"workload": f"{cfg.name}: S={L.S} tokens, M={cfg.M}, H={cfg.H} (H_local={L.Hl}), E={cfg.E} "
+                               f"(G={L.G} local, n_src={L.n_src}), top-{cfg.k}, f={cfg.f}, C={L.C}; "
+                               f"gate+dispatch+FFN+combine fwd+bwd"},
+        "roofline": roofline, "cpu_baseline": cpu,
+        "per_call_ms": {k: round(v, 4) for k, v in per_call.items()},
+    }
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

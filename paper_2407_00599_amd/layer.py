@@ -71,3 +71,97 @@ class MoERankLayer:
         api.moe_gate_bwd(self.dw, self.w, self.idx, self.logits, self.x, self.Wg, S, M, E, k, self.norm_topk,
                          self.dlogits, self.dWg, self.dbias, self.dx, 1, self.ws)
         return self.dx
+
+
+class MoERankShape:
+    """One rank's step at its real shapes when the experts are NOT all local (N_EP > 1 or
+    N_ESP > 1).  The two EP&ESP-AlltoAlls cannot run on one GPU, so the tensors that would
+    arrive through them are caller-provided stand-ins of the right shape:
+        Xrecv  [n_src, G, C, M]    what the first AlltoAll delivers to the local experts
+        Yret   [n_esp, E, C, M]    what the second AlltoAll returns (N_ESP partial sums)
+        dYrecv [n_src, G, C, M]    backward: gradient rows delivered to the local experts
+        dbuf   [n_esp, E, C, M]    backward: input gradients returned to the token owner
+    Every kernel of the path still runs once at the rank's shape; only the data crossing the
+    collectives is synthetic.  With n_src = 1, G = E, n_esp = 1 the stand-ins alias the real
+    buffers and the step is the complete layer."""
+
+    def __init__(self, S_total, M, H, E, k, f, dtype=torch.bfloat16, n_mp=1, mp_idx=0, n_ep=1, n_esp=1,
+                 esp_idx=0, norm_topk=-1, device="cuda:0"):
+        self.S_total, self.M, self.H, self.E, self.k, self.f = S_total, M, H, E, k, f
+        self.n_mp, self.mp_idx, self.n_ep, self.n_esp, self.esp_idx = n_mp, mp_idx, n_ep, n_esp, esp_idx
+        self.norm_topk = norm_topk
+        self.S = S = S_total // n_mp
+        self.C = C = api.moe_capacity(S, E, k, f)
+        self.G = G = E // n_ep
+        self.n_src = n_src = n_ep * n_esp
+        self.Hl = Hl = H // n_esp
+        self.dt = api.MOE_BF16 if dtype == torch.bfloat16 else api.MOE_F32
+        self.closed = (n_src == 1)
+        dev = torch.device(device)
+        i32, f32 = torch.int32, torch.float32
+        e = lambda *shape, dt=dtype: torch.empty(shape, dtype=dt, device=dev)
+        self.logits = e(S, E, dt=f32); self.idx = e(S, k, dt=i32); self.slot = e(S, k, dt=i32)
+        self.w = e(S, k, dt=f32); self.inv = e(E, C, dt=i32); self.counts = e(E, dt=i32)
+        self.buf = e(E, C, M)
+        self.Z = e(n_src, G, C, Hl)
+        self.Yout = e(n_src, G, C, M)
+        self.y = e(S, M)
+        self.dYret = e(E, C, M); self.dw = e(S, k, dt=f32)
+        self.dXout = e(n_src, G, C, M)
+        self.dW1 = e(G, M, H); self.dW2 = e(G, H, M)
+        self.dx = e(S, M); self.dlogits = e(S, E, dt=f32); self.dWg = e(M, E, dt=f32); self.dbias = e(E, dt=f32)
+        if self.closed:
+            self.Xrecv, self.Yret, self.dYrecv, self.dbuf = self.buf.view(1, E, C, M), self.Yout, \
+                self.dYret.view(1, E, C, M), self.dXout
+        else:
+            self.Xrecv = e(n_src, G, C, M); self.Yret = e(n_esp, E, C, M)
+            self.dYrecv = e(n_src, G, C, M); self.dbuf = e(n_esp, E, C, M)
+        nbytes = max(api.moe_gate_workspace_bytes(S, E, k),
+                     api.moe_ffn_workspace_bytes(self.dt, n_src, G, C, M, H, n_esp, 1),
+                     api.moe_gate_bwd_workspace_bytes(S, M, E), 256)
+        self.ws = torch.empty(nbytes, dtype=torch.uint8, device=dev)
+
+    def bind(self, x_full, Wg, bias, W1, W2, dy):
+        S = self.S
+        self.x_full, self.x = x_full, x_full[self.mp_idx * S:(self.mp_idx + 1) * S]
+        self.Wg, self.bias, self.W1, self.W2, self.dy = Wg, bias, W1, W2, dy
+
+    # the individual calls, so a benchmark can time them one by one
+    def gate(self):
+        api.moe_gate_topk(self.x_full, self.Wg, self.bias, self.S_total, self.M, self.E, self.k, self.C, self.mp_idx,
+                          self.n_mp, self.norm_topk, self.logits, self.idx, self.slot, self.w, self.inv, self.counts,
+                          self.ws)
+
+    def dispatch(self):
+        api.moe_dispatch(self.x, self.S, self.M, self.E, self.k, self.C, self.inv, None, self.buf)
+
+    def ffn_fwd(self):
+        api.moe_expert_ffn_fwd(self.Xrecv, self.W1, self.W2, self.n_src, self.G, self.C, self.M, self.H, self.esp_idx,
+                               self.n_esp, self.Z, self.Yout, self.ws)
+
+    def combine(self):
+        api.moe_combine_fwd(self.Yret, self.n_esp, self.S, self.M, self.E, self.k, self.C, self.idx, self.slot,
+                            self.w, self.y)
+
+    def combine_bwd(self):
+        api.moe_combine_bwd(self.dy, self.Yret, self.n_esp, self.S, self.M, self.E, self.k, self.C, self.idx,
+                            self.slot, self.inv, self.w, self.dYret, self.dw)
+
+    def ffn_bwd(self):
+        api.moe_expert_ffn_bwd(self.dYrecv, self.Xrecv, self.Z, self.W1, self.W2, self.n_src, self.G, self.C, self.M,
+                               self.H, self.esp_idx, self.n_esp, self.dXout, self.dW1, self.dW2, self.ws)
+
+    def dispatch_bwd(self):
+        api.moe_combine_fwd(self.dbuf, self.n_esp, self.S, self.M, self.E, self.k, self.C, self.idx, self.slot, None,
+                            self.dx)
+
+    def gate_bwd(self):
+        api.moe_gate_bwd(self.dw, self.w, self.idx, self.logits, self.x, self.Wg, self.S, self.M, self.E, self.k,
+                         self.norm_topk, self.dlogits, self.dWg, self.dbias if self.bias is not None else None,
+                         self.dx, 1, self.ws)
+
+    STEPS = ("gate", "dispatch", "ffn_fwd", "combine", "combine_bwd", "ffn_bwd", "dispatch_bwd", "gate_bwd")
+
+    def step(self):
+        for name in self.STEPS:
+            getattr(self, name)()
