@@ -332,3 +332,26 @@ def layer_bwd(r, dy, x, Wg, W1, W2, k: int, norm_topk: bool, n_esp: int = 1):
     dl, dWg, dbias, dx_gate = gate_bwd(dw, r["logits"], r["idx"], norm_topk, x, Wg)
     return dict(dYret=dYret, dw=dw, dbuf=dbuf, dW1=dW1, dW2=dW2, dlogits=dl, dWg=dWg,
                 dbias=dbias, dx=dx_disp + dx_gate, dx_disp=dx_disp, dx_gate=dx_gate)
+
+
+# --------------------------------------------------------------------------- #
+# The same expert FFN evaluated for single rows / single hidden units, so that
+# outputs of a full-size run can be checked one by one.
+# --------------------------------------------------------------------------- #
+def expert_ffn_rows(x_rows, dy_rows, w1s, w2s):
+    """Rows of ONE expert shard: w1s [M,H_l], w2s [H_l,M].  Returns z, y and dx of those rows."""
+    x = np.asarray(x_rows, F64); dy = np.asarray(dy_rows, F64)
+    w1s = np.asarray(w1s, F64); w2s = np.asarray(w2s, F64)
+    z = x @ w1s
+    y = gelu(z) @ w2s
+    dx = ((dy @ w2s.T) * gelu_grad(z)) @ w1s.T
+    return z, y, dx
+
+
+def expert_ffn_hidden_unit(Xg, dYg, w1_col, w2_row):
+    """One hidden unit h of ONE expert over all of its rows Xg [R,M], dYg [R,M]:
+    returns dW1[:, h] (length M) and dW2[h, :] (length M)."""
+    Xg = np.asarray(Xg, F64); dYg = np.asarray(dYg, F64)
+    z = Xg @ np.asarray(w1_col, F64)
+    dz = (dYg @ np.asarray(w2_row, F64)) * gelu_grad(z)
+    return Xg.T @ dz, gelu(z) @ dYg

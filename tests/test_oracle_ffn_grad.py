@@ -223,3 +223,19 @@ def test_mp_ranks_partition_the_layer_when_nothing_drops():
         assert (rp["slot"] >= 0).all()
         parts.append(rp["y"])
     assert np.allclose(np.concatenate(parts), full["y"], rtol=1e-12, atol=1e-13)
+
+
+def test_row_and_hidden_unit_forms_agree_with_the_full_expert():
+    rng = np.random.default_rng(50)
+    n_src, G, C, M, H = 2, 2, 6, 5, 8
+    X = rng.standard_normal((n_src, G, C, M)); dY = rng.standard_normal((n_src, G, C, M))
+    W1 = rng.standard_normal((G, M, H)); W2 = rng.standard_normal((G, H, M))
+    Z, Y = O.expert_ffn_fwd(X, W1, W2, 1, 2)
+    dX, dW1, dW2 = O.expert_ffn_bwd(dY, X, W1, W2, 1, 2)
+    g = 1
+    w1s, w2s = W1[g][:, 4:], W2[g][4:, :]
+    z, y, dx = O.expert_ffn_rows(X[1, g, 2:4], dY[1, g, 2:4], w1s, w2s)
+    assert np.allclose(z, Z[1, g, 2:4], rtol=1e-13) and np.allclose(y, Y[1, g, 2:4], rtol=1e-12)
+    assert np.allclose(dx, dX[1, g, 2:4], rtol=1e-12, atol=1e-13)
+    a, b = O.expert_ffn_hidden_unit(X[:, g].reshape(-1, M), dY[:, g].reshape(-1, M), w1s[:, 3], w2s[3, :])
+    assert np.allclose(a, dW1[g][:, 3], rtol=1e-12, atol=1e-13) and np.allclose(b, dW2[g][3, :], rtol=1e-12, atol=1e-13)
