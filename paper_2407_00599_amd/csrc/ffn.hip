@@ -27,6 +27,8 @@
 // on one contiguous range of tiles and its L2 sees the same weight panels.
 //
 // fp32 path: a plain LDS-tiled kernel with fp64 accumulation, for the small fp32 configuration.
+#include <type_traits>
+
 #include "common.h"
 
 namespace {
@@ -51,6 +53,7 @@ struct GemmArgs {
   int64_t b_off, c_off;              // constant offset of the ESP slice, elements
   int tiles_m, tiles_n, total_tiles;
   int kchunks;                       // TN: k tiles per chunk = ceil(Cc / 64)
+  uint64_t a_bytes, b_bytes;         // bf16 path: byte sizes of the A and B tensors (buffer descriptors)
 };
 
 __device__ __forceinline__ int64_t phys_row(int r, int g, int G, int Cc) {
@@ -114,6 +117,110 @@ struct Stage {
   uint4 reg[NCH];                                      // NCH == 8*NB (full) or 4 (half)
 };
 
+// Guarded 16-byte loads go through buffer descriptors: a lane that must not load passes an
+// offset beyond num_records and receives zeros, without a branch, so the whole k loop body is
+// one basic block whose loads, LDS traffic and MFMAs can be interleaved.
+typedef unsigned int u32x4_t __attribute__((ext_vector_type(4)));
+constexpr uint32_t OOB = 0xFFFFFFF0u;
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void* base, uint32_t bytes) {
+  return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(base), 0, bytes, 0x00020000);
+}
+__device__ __forceinline__ void pin(uint4& v) {
+  asm volatile("" : "+v"(v.x), "+v"(v.y), "+v"(v.z), "+v"(v.w));
+}
+__device__ __forceinline__ uint4 ldb16(__amdgpu_buffer_rsrc_t r, uint32_t byte_off) {
+  const u32x4_t v = __builtin_amdgcn_raw_buffer_load_b128(r, (int)byte_off, 0, 0);
+  return make_uint4(v.x, v.y, v.z, v.w);
+}
+
+// erf by the rational approximation 7.1.26 of Abramowitz & Stegun (|error| < 1.5e-7), written
+// so that Phi(z) has no cancellation for negative z.  One exp serves GeLU and its derivative.
+__device__ __forceinline__ void gelu_fast(float z, float& g, float& dg) {
+  const float x = fabsf(z) * 0.70710678118654752440f;
+  const float t = __frcp_rn(fmaf(0.3275911f, x, 1.0f));
+  const float ex = __expf(-x * x);  // = exp(-z^2/2)
+  float poly = fmaf(1.061405429f, t, -1.453152027f);
+  poly = fmaf(poly, t, 1.421413741f);
+  poly = fmaf(poly, t, -0.284496736f);
+  poly = fmaf(poly, t, 0.254829592f);
+  const float tail = 0.5f * poly * t * ex;        // = 1 - Phi(|z|)
+  const float cdf = z >= 0.f ? 1.0f - tail : tail;
+  g = z * cdf;
+  dg = fmaf(z * 0.39894228040143267794f, ex, cdf);
+}
+
+// Epilogue shared by the bf16 kernels.  A lane holds, for each 32x32 block (i, j) of its wave
+// tile, output row m = mbase + 32 i + lane%32 and columns n = nbase + 32 j + 8 (q/4) + 4 (lane/32)
+// + q%4 for q = 0..15, i.e. four runs of 4 consecutive columns: 8-byte stores.
+template <int MB, int NBK, int KIND, int EPI>
+__device__ __forceinline__ void store_tile(const GemmArgs& p, f32x16_t (&acc)[MB][NBK], int g, int mbase, int nbase,
+                                           int lane) {
+  bf16_t* __restrict__ Cb = reinterpret_cast<bf16_t*>(p.C);
+  bf16_t* __restrict__ C2b = reinterpret_cast<bf16_t*>(p.C2);
+  const bf16_t* __restrict__ Zb = reinterpret_cast<const bf16_t*>(p.Zin);
+#pragma unroll
+  for (int i = 0; i < MB; ++i) {
+    const int m = mbase + i * 32 + (lane & 31);
+    if (m >= p.Mdim) continue;
+    int64_t crow;
+    if (KIND == KIND_TN) crow = (int64_t)g * p.c_goff + p.c_off + (int64_t)m * p.ldc;
+    else crow = phys_row(m, g, p.G, p.Cc) * p.ldc;
+#pragma unroll
+    for (int j = 0; j < NBK; ++j) {
+#pragma unroll
+      for (int q4 = 0; q4 < 4; ++q4) {
+        const int n = nbase + j * 32 + q4 * 8 + (lane >> 5) * 4;
+        if (n >= p.Ndim) continue;
+        float v[4] = {acc[i][j][q4 * 4 + 0], acc[i][j][q4 * 4 + 1], acc[i][j][q4 * 4 + 2], acc[i][j][q4 * 4 + 3]};
+        if (EPI == EPI_STORE) {
+          *reinterpret_cast<uint2*>(Cb + crow + n) = make_uint2(pack_bf16x2(v[0], v[1]), pack_bf16x2(v[2], v[3]));
+        } else if (EPI == EPI_GELU) {
+          *reinterpret_cast<uint2*>(Cb + crow + n) = make_uint2(pack_bf16x2(v[0], v[1]), pack_bf16x2(v[2], v[3]));
+          float a[4];
+#pragma unroll
+          for (int e = 0; e < 4; ++e) {
+            float dg;
+            gelu_fast(v[e], a[e], dg);
+          }
+          *reinterpret_cast<uint2*>(C2b + crow + n) = make_uint2(pack_bf16x2(a[0], a[1]), pack_bf16x2(a[2], a[3]));
+        } else {
+          const uint2 zq = *reinterpret_cast<const uint2*>(Zb + crow + n);
+          const float z[4] = {__uint_as_float(zq.x << 16), __uint_as_float(zq.x & 0xFFFF0000u),
+                              __uint_as_float(zq.y << 16), __uint_as_float(zq.y & 0xFFFF0000u)};
+          float a[4], d[4];
+#pragma unroll
+          for (int e = 0; e < 4; ++e) {
+            float dg;
+            gelu_fast(z[e], a[e], dg);
+            d[e] = v[e] * dg;
+          }
+          *reinterpret_cast<uint2*>(Cb + crow + n) = make_uint2(pack_bf16x2(d[0], d[1]), pack_bf16x2(d[2], d[3]));
+          *reinterpret_cast<uint2*>(C2b + crow + n) = make_uint2(pack_bf16x2(a[0], a[1]), pack_bf16x2(a[2], a[3]));
+        }
+      }
+    }
+  }
+}
+
+// Instruction-order hints for the scheduler (sched_group_barrier): "N instructions of this
+// class next".  Recipe interleaves NM MFMAs with NA instructions of class MA and NB of class MB.
+enum { SG_MFMA = 0x008, SG_VMEM_READ = 0x020, SG_DS_READ = 0x100, SG_DS_WRITE = 0x200 };
+template <int MASK, int N>
+__device__ __forceinline__ void sched_group() {
+  if constexpr (N > 0) __builtin_amdgcn_sched_group_barrier(MASK, N, 0);
+}
+template <int I, int NM, int NA, int MA, int NB, int MB_>
+struct Recipe {
+  static __device__ __forceinline__ void run() {
+    if constexpr (I < NM) {
+      sched_group<MA, (I + 1) * NA / NM - I * NA / NM>();
+      sched_group<MB_, (I + 1) * NB / NM - I * NB / NM>();
+      sched_group<SG_MFMA, 1>();
+      Recipe<I + 1, NM, NA, MA, NB, MB_>::run();
+    }
+  }
+};
+
 template <int TM, int TN, int WM, int WN, int KIND, int EPI>
 __global__ __launch_bounds__(WM * WN * 64) void ffn_gemm_bf16(const GemmArgs p) {
   constexpr int NT = WM * WN * 64;
@@ -139,87 +246,93 @@ __global__ __launch_bounds__(WM * WN * 64) void ffn_gemm_bf16(const GemmArgs p) 
   const int tm = tr / p.tiles_n, tn = tr - tm * p.tiles_n;
   const int m0 = tm * TM, n0 = tn * TN;
 
-  const bf16_t* __restrict__ Ab = reinterpret_cast<const bf16_t*>(p.A);
-  const bf16_t* __restrict__ Bb = reinterpret_cast<const bf16_t*>(p.B);
+  const int64_t b_base = (int64_t)g * p.b_goff + p.b_off;   // weight-type B: start of expert g's slice
+  // descriptors: activation tensors whole (host guarantees < 4 GiB); weights from expert g's slice on
+  const __amdgpu_buffer_rsrc_t rA = make_rsrc(p.A, (uint32_t)p.a_bytes);
+  const uint64_t b_rem = p.b_bytes - (uint64_t)b_base * 2;
+  const __amdgpu_buffer_rsrc_t rB =
+      (KIND == KIND_TN) ? make_rsrc(p.B, (uint32_t)p.b_bytes)
+                        : make_rsrc(reinterpret_cast<const bf16_t*>(p.B) + b_base,
+                                    b_rem > OOB ? OOB : (uint32_t)b_rem);
 
-  // ---- per-thread staging coordinates ----
-  // direct: row = tid/8 + i*(NT/8), kc = tid%8
-  // transposed: full blocks: kb = bi%8, r8 = bi/8 (bi = tid + i*NT); half: kb4 = tid%16, r8 = tid/16
-  int64_t a_rowoff[SA::NCH];  // direct A: element offset of the row start, -1 = out of range
-  (void)a_rowoff;
+  // ---- per-thread staging coordinates (fixed over the k loop), byte offsets ----
+  // direct:      chunk i -> row = tid/8 + i*(NT/8), k chunk = tid%8
+  // transposed:  full 8x8 blocks: bi = tid + b*NT, kb = bi%8, r8 = bi/8;  half blocks: kb4 = tid%16, r8 = tid/16
+  uint32_t a_off[A_TR ? 1 : SA::NCH];
   if (!A_TR) {
 #pragma unroll
     for (int i = 0; i < SA::NCH; ++i) {
       const int r = m0 + (tid >> 3) + i * (NT / 8);
-      a_rowoff[i] = (r < p.Mdim) ? phys_row(r, g, p.G, p.Cc) * p.lda : -1;
+      a_off[i] = (r < p.Mdim) ? (uint32_t)((phys_row(r, g, p.G, p.Cc) * p.lda + (tid & 7) * 8) * 2) : OOB;
     }
   }
-  const int64_t b_base = (int64_t)g * p.b_goff + p.b_off;
-
+  uint32_t b_off[B_TR ? 1 : SB::NCH];
+  if (!B_TR) {
+#pragma unroll
+    for (int i = 0; i < SB::NCH; ++i) {
+      const int n = n0 + (tid >> 3) + i * (NT / 8);
+      b_off[i] = (n < p.Ndim) ? (uint32_t)(((int64_t)n * p.ldb + (tid & 7) * 8) * 2) : OOB;
+    }
+  }
   const int nk = (KIND == KIND_TN) ? p.n_src * p.kchunks : (p.Kdim + KT - 1) / KT;
+  const uint32_t lda2 = (uint32_t)(p.lda * 2), ldb2 = (uint32_t)(p.ldb * 2);
 
   SA sa;
   SB sb;
 
+  // global -> registers for k tile kt; kt >= nk loads nothing (all lanes out of range)
   auto load_tiles = [&](int kt) {
+    const bool live = kt < nk;
     // ---------------- A ----------------
     if (!A_TR) {
-      const int k = kt * KT + (tid & 7) * 8;
+      const int k0 = kt * KT;
+      const bool kok = live && k0 + (tid & 7) * 8 < p.Kdim;
 #pragma unroll
-      for (int i = 0; i < SA::NCH; ++i) {
-        const bool ok = a_rowoff[i] >= 0 && k < p.Kdim;
-        sa.reg[i] = ok ? *reinterpret_cast<const uint4*>(Ab + a_rowoff[i] + k) : make_uint4(0, 0, 0, 0);
-      }
+      for (int i = 0; i < SA::NCH; ++i)
+        sa.reg[i] = ldb16(rA, (kok && a_off[i] != OOB) ? a_off[i] + (uint32_t)k0 * 2u : OOB);
     } else {
       const int s = kt / p.kchunks;
       const int c0 = (kt - s * p.kchunks) * KT;
-      const int64_t chunk_row = ((int64_t)s * p.G + g) * p.Cc;
+      const int64_t chunk_row = ((int64_t)s * p.G + g) * p.Cc + c0;
+      const int klim = live ? p.Cc - c0 : 0;
       if (!SA::HALF) {
 #pragma unroll
         for (int b = 0; b < SA::NB; ++b) {
           const int bi = tid + b * NT;
           const int kb = bi & 7, r8 = bi >> 3;
           const int col = m0 + r8 * 8;
+          const uint32_t off0 = (uint32_t)(((chunk_row + kb * 8) * p.lda + col) * 2);
 #pragma unroll
-          for (int i = 0; i < 8; ++i) {
-            const int c = c0 + kb * 8 + i;
-            const bool ok = c < p.Cc && col < p.Mdim;
-            sa.reg[b * 8 + i] = ok ? *reinterpret_cast<const uint4*>(Ab + (chunk_row + c) * p.lda + col)
-                                   : make_uint4(0, 0, 0, 0);
-          }
+          for (int i = 0; i < 8; ++i)
+            sa.reg[b * 8 + i] = ldb16(rA, (kb * 8 + i < klim && col < p.Mdim) ? off0 + i * lda2 : OOB);
         }
       } else {
         const int kb4 = tid & 15, r8 = tid >> 4;
         const int col = m0 + r8 * 8;
+        const uint32_t off0 = (uint32_t)(((chunk_row + kb4 * 4) * p.lda + col) * 2);
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-          const int c = c0 + kb4 * 4 + i;
-          const bool ok = c < p.Cc && col < p.Mdim;
-          sa.reg[i] = ok ? *reinterpret_cast<const uint4*>(Ab + (chunk_row + c) * p.lda + col)
-                         : make_uint4(0, 0, 0, 0);
-        }
+        for (int i = 0; i < 4; ++i)
+          sa.reg[i] = ldb16(rA, (kb4 * 4 + i < klim && col < p.Mdim) ? off0 + i * lda2 : OOB);
       }
     }
     // ---------------- B ----------------
     if (!B_TR) {  // NT: weight rows n, k contiguous
-      const int k = kt * KT + (tid & 7) * 8;
+      const int k0 = kt * KT;
+      const bool kok = live && k0 + (tid & 7) * 8 < p.Kdim;
 #pragma unroll
-      for (int i = 0; i < SB::NCH; ++i) {
-        const int n = n0 + (tid >> 3) + i * (NT / 8);
-        const bool ok = n < p.Ndim && k < p.Kdim;
-        sb.reg[i] = ok ? *reinterpret_cast<const uint4*>(Bb + b_base + (int64_t)n * p.ldb + k) : make_uint4(0, 0, 0, 0);
-      }
+      for (int i = 0; i < SB::NCH; ++i)
+        sb.reg[i] = ldb16(rB, (kok && b_off[i] != OOB) ? b_off[i] + (uint32_t)k0 * 2u : OOB);
     } else {
-      int64_t krow0;  // element offset of k row 0 of this tile
-      int klim;       // number of valid k rows in this tile
+      uint32_t krow0;  // byte offset of k row 0 of this tile (relative to the descriptor base)
+      int klim;        // number of valid k rows in this tile
       if (KIND == KIND_NN) {
-        krow0 = b_base + (int64_t)kt * KT * p.ldb;
-        klim = p.Kdim - kt * KT;
+        krow0 = (uint32_t)((int64_t)kt * KT * p.ldb * 2);
+        klim = live ? p.Kdim - kt * KT : 0;
       } else {
         const int s = kt / p.kchunks;
         const int c0 = (kt - s * p.kchunks) * KT;
-        krow0 = (((int64_t)s * p.G + g) * p.Cc + c0) * p.ldb;
-        klim = p.Cc - c0;
+        krow0 = (uint32_t)((((int64_t)s * p.G + g) * p.Cc + c0) * p.ldb * 2);
+        klim = live ? p.Cc - c0 : 0;
       }
       if (!SB::HALF) {
 #pragma unroll
@@ -227,31 +340,24 @@ __global__ __launch_bounds__(WM * WN * 64) void ffn_gemm_bf16(const GemmArgs p) 
           const int bi = tid + b * NT;
           const int kb = bi & 7, r8 = bi >> 3;
           const int col = n0 + r8 * 8;
+          const uint32_t off0 = krow0 + (uint32_t)(kb * 8) * ldb2 + (uint32_t)col * 2u;
 #pragma unroll
-          for (int i = 0; i < 8; ++i) {
-            const int kk = kb * 8 + i;
-            const bool ok = kk < klim && col < p.Ndim;
-            sb.reg[b * 8 + i] = ok ? *reinterpret_cast<const uint4*>(Bb + krow0 + (int64_t)kk * p.ldb + col)
-                                   : make_uint4(0, 0, 0, 0);
-          }
+          for (int i = 0; i < 8; ++i)
+            sb.reg[b * 8 + i] = ldb16(rB, (kb * 8 + i < klim && col < p.Ndim) ? off0 + i * ldb2 : OOB);
         }
       } else {
         const int kb4 = tid & 15, r8 = tid >> 4;
         const int col = n0 + r8 * 8;
+        const uint32_t off0 = krow0 + (uint32_t)(kb4 * 4) * ldb2 + (uint32_t)col * 2u;
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-          const int kk = kb4 * 4 + i;
-          const bool ok = kk < klim && col < p.Ndim;
-          sb.reg[i] = ok ? *reinterpret_cast<const uint4*>(Bb + krow0 + (int64_t)kk * p.ldb + col)
-                         : make_uint4(0, 0, 0, 0);
-        }
+        for (int i = 0; i < 4; ++i)
+          sb.reg[i] = ldb16(rB, (kb4 * 4 + i < klim && col < p.Ndim) ? off0 + i * ldb2 : OOB);
       }
     }
   };
 
-  auto store_tiles = [&](int buf) {
+  auto store_A = [&](int buf) {
     bf16_t* As = smem + buf * (TM + TN) * PITCH;
-    bf16_t* Bs = As + TM * PITCH;
     if (!A_TR) {
 #pragma unroll
       for (int i = 0; i < SA::NCH; ++i) {
@@ -275,6 +381,9 @@ __global__ __launch_bounds__(WM * WN * 64) void ffn_gemm_bf16(const GemmArgs p) 
 #pragma unroll
       for (int n = 0; n < 8; ++n) *reinterpret_cast<uint2*>(As + (r8 * 8 + n) * PITCH + kb4 * 4) = t[n];
     }
+  };
+  auto store_B = [&](int buf) {
+    bf16_t* Bs = smem + buf * (TM + TN) * PITCH + TM * PITCH;
     if (!B_TR) {
 #pragma unroll
       for (int i = 0; i < SB::NCH; ++i) {
@@ -308,77 +417,336 @@ __global__ __launch_bounds__(WM * WN * 64) void ffn_gemm_bf16(const GemmArgs p) 
 #pragma unroll
       for (int q = 0; q < 16; ++q) acc[i][j][q] = 0.f;
 
-  load_tiles(0);
-  store_tiles(0);
-  __syncthreads();
+  // fragment addresses of this lane inside a stage
+  const int a_frag = (wm * TMW + (lane & 31)) * PITCH + (lane >> 5) * 8;
+  const int b_frag = TM * PITCH + (wn * TNW + (lane & 31)) * PITCH + (lane >> 5) * 8;
+  bf16x8_t fa[2][MB], fb[2][NBK];
+  auto load_frags = [&](int buf, int kk, int set) {
+    const bf16_t* st = smem + buf * (TM + TN) * PITCH + kk * 16;
+#pragma unroll
+    for (int i = 0; i < MB; ++i) fa[set][i] = *reinterpret_cast<const bf16x8_t*>(st + a_frag + i * 32 * PITCH);
+#pragma unroll
+    for (int j = 0; j < NBK; ++j) fb[set][j] = *reinterpret_cast<const bf16x8_t*>(st + b_frag + j * 32 * PITCH);
+  };
 
+  constexpr int NWA = A_TR ? 8 * (SA::HALF ? 1 : SA::NB) : SA::NCH;   // LDS writes per tile, A / B
+  constexpr int NWB = B_TR ? 8 * (SB::HALF ? 1 : SB::NB) : SB::NCH;
+  load_tiles(0);
+  store_A(0);
+  store_B(0);
+  __syncthreads();
+  load_frags(0, 0, 0);
+
+  // One k tile per iteration; the body is branch-free.  sched_barrier(0) fences keep the order
+  // written here: global loads of the next tile first (a whole tile of MFMAs hides their
+  // latency), fragment reads of step kk+1 issued before the MFMAs of step kk, LDS writes of the
+  // next tile riding on the last two MFMA groups.
   for (int kt = 0; kt < nk; ++kt) {
     const int buf = kt & 1;
-    if (kt + 1 < nk) load_tiles(kt + 1);
-    const bf16_t* As = smem + buf * (TM + TN) * PITCH + (wm * TMW + (lane & 31)) * PITCH + (lane >> 5) * 8;
-    const bf16_t* Bs = smem + buf * (TM + TN) * PITCH + TM * PITCH + (wn * TNW + (lane & 31)) * PITCH + (lane >> 5) * 8;
 #pragma unroll
     for (int kk = 0; kk < KT / 16; ++kk) {
-      bf16x8_t af[MB], bfr[NBK];
+      const int cur = kk & 1;
+      if (kk + 1 < KT / 16) load_frags(buf, kk + 1, cur ^ 1);
+      __builtin_amdgcn_sched_barrier(0);
+      if (kk == 0) load_tiles(kt + 1);
+      // the empty asm pins the staged registers here, so the transposes that consume them are
+      // not hoisted up to the loads (where they would wait for memory)
+      if (kk == KT / 16 - 2) {
 #pragma unroll
-      for (int i = 0; i < MB; ++i) af[i] = *reinterpret_cast<const bf16x8_t*>(As + i * 32 * PITCH + kk * 16);
+        for (int i = 0; i < SA::NCH; ++i) pin(sa.reg[i]);
+        store_A(buf ^ 1);
+      }
+      if (kk == KT / 16 - 1) {
 #pragma unroll
-      for (int j = 0; j < NBK; ++j) bfr[j] = *reinterpret_cast<const bf16x8_t*>(Bs + j * 32 * PITCH + kk * 16);
+        for (int i = 0; i < SB::NCH; ++i) pin(sb.reg[i]);
+        store_B(buf ^ 1);
+      }
 #pragma unroll
       for (int i = 0; i < MB; ++i)
 #pragma unroll
         for (int j = 0; j < NBK; ++j)
-          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[j], af[i], acc[i][j], 0, 0, 0);
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[cur][j], fa[cur][i], acc[i][j], 0, 0, 0);
+      // inside the fenced group: one memory instruction per MFMA, so that issuing the loads /
+      // LDS writes never holds up the matrix pipe
+      constexpr int NM = MB * NBK;
+      if (kk == 0) Recipe<0, NM, SA::NCH + SB::NCH, SG_VMEM_READ, 0, SG_DS_READ>::run();
+      if (kk == KT / 16 - 2) Recipe<0, NM, NWA, SG_DS_WRITE, 0, SG_DS_READ>::run();
+      if (kk == KT / 16 - 1) Recipe<0, NM, NWB, SG_DS_WRITE, 0, SG_DS_READ>::run();
+      __builtin_amdgcn_sched_barrier(0);
     }
-    if (kt + 1 < nk) store_tiles(buf ^ 1);
     __syncthreads();
+    load_frags(buf ^ 1, 0, 0);
   }
 
-  // ---- epilogue: lane holds output row m = .. + lane%32 and, for q = 0..15,
-  //      column n = .. + 8*(q/4) + 4*(lane/32) + q%4 ----
-  bf16_t* __restrict__ Cb = reinterpret_cast<bf16_t*>(p.C);
-  bf16_t* __restrict__ C2b = reinterpret_cast<bf16_t*>(p.C2);
-  const bf16_t* __restrict__ Zb = reinterpret_cast<const bf16_t*>(p.Zin);
+  store_tile<MB, NBK, KIND, EPI>(p, acc, g, m0 + wm * TMW, n0 + wn * TNW, lane);
+}
+
+// ------------------------------------------------------------------------------------------
+// bf16 MFMA kernel with an LDS-DMA pipeline (the fast path for large GEMMs).
+//
+// 256x256 output tile, 4 waves (2x2), 128x128 per wave, k tile 32, four LDS stages of 32 KiB.
+// Global memory goes straight to LDS (buffer_load ... lds, 16 bytes per lane, no VGPR staging, no
+// ds_write): a wave instruction fills 1 KiB of consecutive 16-byte slots in lane order, so the
+// tile is stored unpadded and bank conflicts are avoided by permuting WHICH 16-byte chunk of a
+// row each lane fetches (an XOR swizzle that the fragment reads undo).  Lanes whose row / column
+// / k index is out of range pass an out-of-range buffer offset; the hardware then writes zeros.
+//   operand with k contiguous in memory : stage holds [row][32 k] (64 B rows, 4 chunks), chunk c
+//       of row r sits in slot c ^ ((r >> 2) & 3); fragments are read with ds_read_b128.
+//   operand with k as the slow index    : stage holds [32 k][256 cols] (512 B rows, 32 chunks),
+//       chunk c of k-row k sits in slot c ^ (2 (k & 3)); fragments are read with the transposing
+//       LDS load ds_read_b64_tr_b16: a 16-lane group reads a 4(k) x 16(col) patch (lane s: k-row
+//       s/4, 8-byte piece s%4) and lane i receives the 4 k-values of column i.
+// Pipeline: tile t+3 is requested while tile t is multiplied.  Once per k tile, between its two
+// 16-wide MFMA steps, each wave waits until its own requests for tile t+1 have landed
+// (s_waitcnt vmcnt), all waves meet at a barrier, and the stage freed by tile t-1 is refilled.
+// Because the barrier sits in the middle, the first fragments of tile t+1 are fetched under
+// the second MFMA step and no LDS latency is exposed at the tile boundary.
+// ------------------------------------------------------------------------------------------
+#define LDS_AS __attribute__((address_space(3)))
+typedef short s16x4_t __attribute__((ext_vector_type(4)));
+
+constexpr int DT = 256;                    // tile edge
+constexpr int DK = 32;                     // k tile
+constexpr int DSTAGES = 4;
+constexpr int DREGION = DT * DK * 2;       // bytes per operand per stage (16 KiB)
+constexpr int DSTAGE = 2 * DREGION;
+
+__device__ __forceinline__ void dma16(__amdgpu_buffer_rsrc_t r, bf16_t* lds_wave_base, uint32_t byte_off) {
+  __builtin_amdgcn_raw_ptr_buffer_load_lds(r, (LDS_AS void*)lds_wave_base, 16, (int)byte_off, 0, 0, 0);
+}
+// Fragment reads are issued as volatile asm: the compiler then neither reorders them nor guards
+// them with conservative waits against the LDS-DMA requests in flight.  The kernel waits for them
+// itself (s_waitcnt lgkmcnt(0)) and passes the registers through ready() before the MFMAs use them.
+typedef unsigned int u32x2_t __attribute__((ext_vector_type(2)));
+union Frag {
+  bf16x8_t v;
+  u32x4_t q;
+  u32x2_t h[2];
+};
+template <int OFF>
+__device__ __forceinline__ void lds_read_kc(Frag& f, uint32_t addr) {
+  asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(f.q) : "v"(addr), "n"(OFF));
+}
+template <int OFF>
+__device__ __forceinline__ void lds_read_nc(Frag& f, uint32_t addr_lo, uint32_t addr_hi) {
+  asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(f.h[0]) : "v"(addr_lo), "n"(OFF));
+  asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(f.h[1]) : "v"(addr_hi), "n"(OFF));
+}
+__device__ __forceinline__ void ready(Frag& f) { asm volatile("" : "+v"(f.q)); }
+
+template <int KIND, int EPI>
+__global__ __launch_bounds__(256) void ffn_gemm_dma(const GemmArgs p) {
+  constexpr bool A_NC = (KIND == KIND_TN);                     // A has k as the slow index
+  constexpr bool B_NC = (KIND == KIND_NN || KIND == KIND_TN);  // B has k as the slow index
+  constexpr int MB = 4, NBK = 4;
+
+  __shared__ __attribute__((aligned(1024))) char smem[DSTAGES * DSTAGE];
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wm = wave >> 1, wn = wave & 1;
+
+  const int per_xcd = (p.total_tiles + 7) / 8;
+  const int tile = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
+  if (tile >= p.total_tiles) return;
+  const int tiles_per_g = p.tiles_m * p.tiles_n;
+  const int g = tile / tiles_per_g;
+  const int tr = tile - g * tiles_per_g;
+  const int tm = tr / p.tiles_n, tn = tr - tm * p.tiles_n;
+  const int m0 = tm * DT, n0 = tn * DT;
+
+  const int64_t b_base = (int64_t)g * p.b_goff + p.b_off;
+  const __amdgpu_buffer_rsrc_t rA = make_rsrc(p.A, (uint32_t)p.a_bytes);
+  const uint64_t b_rem = p.b_bytes - (uint64_t)b_base * 2;
+  const __amdgpu_buffer_rsrc_t rB =
+      (KIND == KIND_TN) ? make_rsrc(p.B, (uint32_t)p.b_bytes)
+                        : make_rsrc(reinterpret_cast<const bf16_t*>(p.B) + b_base, b_rem > OOB ? OOB : (uint32_t)b_rem);
+
+  const int kpc = (p.Cc + DK - 1) / DK;  // TN: k tiles per chunk
+  const int nk = (KIND == KIND_TN) ? p.n_src * kpc : (p.Kdim + DK - 1) / DK;
+
+  // ---- per-lane request coordinates: each wave issues 4 requests per operand per k tile ----
+  // k-contiguous operand, request q = 4 wave + j: rows 16 q + lane/4, slot lane%4 holds logical chunk kc_c
+  const int kc_c = (lane & 3) ^ ((lane >> 4) & 3);
+  // k-slow operand, request q: k-rows 2 q + lane/32, slot lane%32 holds logical chunk nc_c[j]
+  uint32_t a_req[4], b_req[4];   // byte offset of the lane's 16 bytes at k tile 0, or OOB
+  int a_k[4], b_k[4];            // k index (within the k tile) this request covers (k-slow), or first k (k-contig)
 #pragma unroll
-  for (int i = 0; i < MB; ++i) {
-    const int m = m0 + wm * TMW + i * 32 + (lane & 31);
-    if (m >= p.Mdim) continue;
-    int64_t crow;
-    if (KIND == KIND_TN) crow = (int64_t)g * p.c_goff + p.c_off + (int64_t)m * p.ldc;
-    else crow = phys_row(m, g, p.G, p.Cc) * p.ldc;
-#pragma unroll
-    for (int j = 0; j < NBK; ++j) {
-#pragma unroll
-      for (int q4 = 0; q4 < 4; ++q4) {
-        const int n = n0 + wn * TNW + j * 32 + q4 * 8 + (lane >> 5) * 4;
-        if (n >= p.Ndim) continue;
-        float v[4] = {acc[i][j][q4 * 4 + 0], acc[i][j][q4 * 4 + 1], acc[i][j][q4 * 4 + 2], acc[i][j][q4 * 4 + 3]};
-        if (EPI == EPI_STORE) {
-          *reinterpret_cast<uint2*>(Cb + crow + n) = make_uint2(pack_bf16x2(v[0], v[1]), pack_bf16x2(v[2], v[3]));
-        } else if (EPI == EPI_GELU) {
-          *reinterpret_cast<uint2*>(Cb + crow + n) = make_uint2(pack_bf16x2(v[0], v[1]), pack_bf16x2(v[2], v[3]));
-          float a[4];
-#pragma unroll
-          for (int e = 0; e < 4; ++e) a[e] = gelu_f(v[e]);
-          *reinterpret_cast<uint2*>(C2b + crow + n) = make_uint2(pack_bf16x2(a[0], a[1]), pack_bf16x2(a[2], a[3]));
-        } else {
-          const uint2 zq = *reinterpret_cast<const uint2*>(Zb + crow + n);
-          const float z[4] = {__uint_as_float(zq.x << 16), __uint_as_float(zq.x & 0xFFFF0000u),
-                              __uint_as_float(zq.y << 16), __uint_as_float(zq.y & 0xFFFF0000u)};
-          float a[4], d[4];
-#pragma unroll
-          for (int e = 0; e < 4; ++e) {
-            float ge, dg;
-            gelu_and_grad(z[e], ge, dg);
-            a[e] = ge;
-            d[e] = v[e] * dg;
-          }
-          *reinterpret_cast<uint2*>(Cb + crow + n) = make_uint2(pack_bf16x2(d[0], d[1]), pack_bf16x2(d[2], d[3]));
-          *reinterpret_cast<uint2*>(C2b + crow + n) = make_uint2(pack_bf16x2(a[0], a[1]), pack_bf16x2(a[2], a[3]));
-        }
-      }
+  for (int j = 0; j < 4; ++j) {
+    const int q = wave * 4 + j;
+    if (!A_NC) {
+      const int r = m0 + q * 16 + (lane >> 2);
+      a_k[j] = kc_c * 8;
+      a_req[j] = (r < p.Mdim) ? (uint32_t)((phys_row(r, g, p.G, p.Cc) * p.lda + kc_c * 8) * 2) : OOB;
+    } else {
+      const int k = 2 * q + (lane >> 5);
+      const int col = m0 + (((lane & 31) ^ (2 * (k & 3))) * 8);
+      a_k[j] = k;
+      a_req[j] = (col < p.Mdim) ? (uint32_t)(((int64_t)k * p.lda + col) * 2) : OOB;
+    }
+    if (!B_NC) {
+      const int n = n0 + q * 16 + (lane >> 2);
+      b_k[j] = kc_c * 8;
+      b_req[j] = (n < p.Ndim) ? (uint32_t)(((int64_t)n * p.ldb + kc_c * 8) * 2) : OOB;
+    } else {
+      const int k = 2 * q + (lane >> 5);
+      const int col = n0 + (((lane & 31) ^ (2 * (k & 3))) * 8);
+      b_k[j] = k;
+      b_req[j] = (col < p.Ndim) ? (uint32_t)(((int64_t)k * p.ldb + col) * 2) : OOB;
     }
   }
+
+  // requests of k tile kt into its stage; tiles past the end still issue (all lanes out of range)
+  // so that the number of outstanding requests per wave is the same in every iteration
+  auto request = [&](int kt) {
+    char* st = smem + (kt & (DSTAGES - 1)) * DSTAGE;
+    const bool live = kt < nk;
+    uint32_t a_add, b_add;   // byte offset of the k tile
+    int a_lim, b_lim;        // valid k count in this tile
+    if (KIND == KIND_TN) {
+      const int s = kt / kpc;
+      const int c0 = (kt - s * kpc) * DK;
+      const int64_t row0 = ((int64_t)s * p.G + g) * p.Cc + c0;
+      a_add = (uint32_t)(row0 * p.lda * 2);
+      b_add = (uint32_t)(row0 * p.ldb * 2);
+      a_lim = b_lim = live ? p.Cc - c0 : 0;
+    } else {
+      a_add = (uint32_t)kt * (DK * 2);
+      b_add = B_NC ? (uint32_t)((int64_t)kt * DK * p.ldb * 2) : (uint32_t)kt * (DK * 2);
+      a_lim = b_lim = live ? p.Kdim - kt * DK : 0;
+    }
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const int q = wave * 4 + j;
+      dma16(rA, reinterpret_cast<bf16_t*>(st + q * 1024), (a_req[j] != OOB && a_k[j] < a_lim) ? a_req[j] + a_add : OOB);
+    }
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const int q = wave * 4 + j;
+      dma16(rB, reinterpret_cast<bf16_t*>(st + DREGION + q * 1024),
+            (b_req[j] != OOB && b_k[j] < b_lim) ? b_req[j] + b_add : OOB);
+    }
+  };
+
+  // ---- per-lane fragment addresses inside a stage (bytes), for k step kk = 0; kk = 1 adds a constant ----
+  // k-contiguous: row = base + 32 i + lane%32, logical chunk 2 kk + lane/32  -> slot ^ ((row >> 2) & 3)
+  // k-slow: 16-lane group b = lane/16, s = lane%16: k = 16 kk + 8 (b/2) + 4 h + s/4,
+  //         col = base + 32 j + 16 (b%2) + 4 (s%4); chunk = col/8 ^ 2 (s/4), piece = (s%4)&1
+  // k-contiguous: a_fr[kk][0]; k-slow: a_fr[h][parity of the 32-column block] (the swizzle touches the
+  // chunk-index bit that an odd block offset sets, so odd blocks get their own base address)
+  uint32_t a_fr[2][2], b_fr[2][2];
+  {
+    const int b = lane >> 4, s = lane & 15;
+    if (!A_NC) {
+      const int row = wm * 128 + (lane & 31);
+      for (int kk = 0; kk < 2; ++kk)
+        a_fr[kk][0] = a_fr[kk][1] = row * 64 + (((2 * kk + (lane >> 5)) ^ ((lane >> 2) & 3)) * 16);
+    } else {
+      for (int h = 0; h < 2; ++h)
+        for (int par = 0; par < 2; ++par) {
+          const int col = wm * 128 + 32 * par + 16 * (b & 1) + 4 * (s & 3);
+          const int k = 8 * (b >> 1) + 4 * h + (s >> 2);
+          a_fr[h][par] = k * 512 + (((col >> 3) ^ (2 * (s >> 2))) * 16) + ((s & 1) * 8);
+        }
+    }
+    if (!B_NC) {
+      const int row = wn * 128 + (lane & 31);
+      for (int kk = 0; kk < 2; ++kk)
+        b_fr[kk][0] = b_fr[kk][1] = DREGION + row * 64 + (((2 * kk + (lane >> 5)) ^ ((lane >> 2) & 3)) * 16);
+    } else {
+      for (int h = 0; h < 2; ++h)
+        for (int par = 0; par < 2; ++par) {
+          const int col = wn * 128 + 32 * par + 16 * (b & 1) + 4 * (s & 3);
+          const int k = 8 * (b >> 1) + 4 * h + (s >> 2);
+          b_fr[h][par] = DREGION + k * 512 + (((col >> 3) ^ (2 * (s >> 2))) * 16) + ((s & 1) * 8);
+        }
+    }
+  }
+  Frag fa[2][MB], fb[2][NBK];
+  const uint32_t lds0 = (uint32_t)(uintptr_t)(LDS_AS char*)smem;
+  // set = kk: fragments of k step kk of tile kt
+  auto load_frags = [&](int kt, auto kk_tag) {
+    constexpr int kk = decltype(kk_tag)::value;
+    const uint32_t st = lds0 + (uint32_t)(kt & (DSTAGES - 1)) * DSTAGE;
+    if (!A_NC) {
+      lds_read_kc<0 * 2048>(fa[kk][0], st + a_fr[kk][0]); lds_read_kc<1 * 2048>(fa[kk][1], st + a_fr[kk][0]);
+      lds_read_kc<2 * 2048>(fa[kk][2], st + a_fr[kk][0]); lds_read_kc<3 * 2048>(fa[kk][3], st + a_fr[kk][0]);
+    } else {
+      lds_read_nc<kk * 8192 + 0>(fa[kk][0], st + a_fr[0][0], st + a_fr[1][0]);
+      lds_read_nc<kk * 8192 + 0>(fa[kk][1], st + a_fr[0][1], st + a_fr[1][1]);
+      lds_read_nc<kk * 8192 + 128>(fa[kk][2], st + a_fr[0][0], st + a_fr[1][0]);
+      lds_read_nc<kk * 8192 + 128>(fa[kk][3], st + a_fr[0][1], st + a_fr[1][1]);
+    }
+    if (!B_NC) {
+      lds_read_kc<0 * 2048>(fb[kk][0], st + b_fr[kk][0]); lds_read_kc<1 * 2048>(fb[kk][1], st + b_fr[kk][0]);
+      lds_read_kc<2 * 2048>(fb[kk][2], st + b_fr[kk][0]); lds_read_kc<3 * 2048>(fb[kk][3], st + b_fr[kk][0]);
+    } else {
+      lds_read_nc<kk * 8192 + 0>(fb[kk][0], st + b_fr[0][0], st + b_fr[1][0]);
+      lds_read_nc<kk * 8192 + 0>(fb[kk][1], st + b_fr[0][1], st + b_fr[1][1]);
+      lds_read_nc<kk * 8192 + 128>(fb[kk][2], st + b_fr[0][0], st + b_fr[1][0]);
+      lds_read_nc<kk * 8192 + 128>(fb[kk][3], st + b_fr[0][1], st + b_fr[1][1]);
+    }
+  };
+  auto frags_ready = [&](int set) {
+    __builtin_amdgcn_s_waitcnt(0xC07F);  // lgkmcnt(0)
+#pragma unroll
+    for (int i = 0; i < MB; ++i) ready(fa[set][i]);
+#pragma unroll
+    for (int j = 0; j < NBK; ++j) ready(fb[set][j]);
+  };
+  using K0 = std::integral_constant<int, 0>;
+  using K1 = std::integral_constant<int, 1>;
+
+  f32x16_t acc[MB][NBK];
+#pragma unroll
+  for (int i = 0; i < MB; ++i)
+#pragma unroll
+    for (int j = 0; j < NBK; ++j)
+#pragma unroll
+      for (int q = 0; q < 16; ++q) acc[i][j][q] = 0.f;
+
+  request(0);
+  request(1);
+  request(2);
+  __builtin_amdgcn_s_waitcnt(0x4F70);  // vmcnt(16): this wave's requests for tile 0 have landed
+  __builtin_amdgcn_s_barrier();
+  load_frags(0, K0{});
+
+  auto mfma_rows = [&](int set, int i_begin, int i_end) {
+#pragma unroll
+    for (int i = 0; i < MB; ++i) {
+      if (i < i_begin || i >= i_end) continue;
+#pragma unroll
+      for (int j = 0; j < NBK; ++j)
+        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[set][j].v, fa[set][i].v, acc[i][j], 0, 0, 0);
+    }
+  };
+  for (int kt = 0; kt < nk; ++kt) {
+    // ---- first k step of tile kt; its fragments were requested half a tile ago ----
+    frags_ready(0);
+    __builtin_amdgcn_sched_barrier(0);
+    mfma_rows(0, 0, 1);                  // a few MFMAs first, so the reads below issue in their shadow
+    __builtin_amdgcn_sched_barrier(0);
+    load_frags(kt, K1{});
+    __builtin_amdgcn_sched_barrier(0);
+    mfma_rows(0, 1, MB);
+    __builtin_amdgcn_sched_barrier(0);
+    // ---- second k step; in its shadow: barrier, first fragments of tile kt+1, requests of tile kt+3 ----
+    frags_ready(1);
+    __builtin_amdgcn_sched_barrier(0);
+    mfma_rows(1, 0, 1);
+    __builtin_amdgcn_sched_barrier(0);
+    __builtin_amdgcn_s_waitcnt(0x0F78);  // vmcnt(8): tile kt+1 has landed (tile kt+2 may be in flight)
+    __builtin_amdgcn_s_barrier();        // everyone is past tile kt-1, and tile kt+1 is complete
+    __builtin_amdgcn_sched_barrier(0);
+    load_frags(kt + 1, K0{});
+    __builtin_amdgcn_sched_barrier(0);
+    request(kt + 3);                     // refills the stage of tile kt-1
+    mfma_rows(1, 1, MB);
+    __builtin_amdgcn_sched_barrier(0);
+  }
+  __builtin_amdgcn_s_waitcnt(0x0070);  // drain trailing (empty) requests and fragment reads before LDS is released
+
+  store_tile<MB, NBK, KIND, EPI>(p, acc, g, m0 + wm * 128, n0 + wn * 128, lane);
 }
 
 // ------------------------------------------------------------------------------------------
@@ -491,16 +859,23 @@ void launch_gemm(GemmArgs a, int dtype, hipStream_t st) {
     return;
   }
   a.kchunks = (a.Cc + KT - 1) / KT;
+  const uint64_t act_rows = (uint64_t)a.n_src * a.G * a.Cc;
+  a.a_bytes = act_rows * (uint64_t)a.lda * 2;
+  a.b_bytes = (KIND == KIND_TN) ? act_rows * (uint64_t)a.ldb * 2 : (uint64_t)a.G * (uint64_t)a.b_goff * 2;
   const int64_t big_tiles = (int64_t)a.G * ((a.Mdim + 255) / 256) * ((a.Ndim + 255) / 256);
   bool big = big_tiles >= 512;
   if (g_tile_pref == 1) big = false;
-  if (g_tile_pref == 2) big = true;
+  if (g_tile_pref >= 2) big = true;
   const int T = big ? 256 : 128;
   a.tiles_m = (a.Mdim + T - 1) / T;
   a.tiles_n = (a.Ndim + T - 1) / T;
   a.total_tiles = a.G * a.tiles_m * a.tiles_n;
   const dim3 grid((unsigned)(((a.total_tiles + 7) / 8) * 8));
-  if (big) hipLaunchKernelGGL((ffn_gemm_bf16<256, 256, 2, 2, KIND, EPI>), grid, dim3(256), 0, st, a);
+  if (big && g_tile_pref != 3 && g_tile_pref != 4 && g_tile_pref != 5)
+    hipLaunchKernelGGL((ffn_gemm_dma<KIND, EPI>), grid, dim3(256), 0, st, a);
+  else if (big && g_tile_pref == 3) hipLaunchKernelGGL((ffn_gemm_bf16<256, 256, 2, 4, KIND, EPI>), grid, dim3(512), 0, st, a);
+  else if (big && g_tile_pref == 4) hipLaunchKernelGGL((ffn_gemm_bf16<256, 256, 4, 2, KIND, EPI>), grid, dim3(512), 0, st, a);
+  else if (big) hipLaunchKernelGGL((ffn_gemm_bf16<256, 256, 2, 2, KIND, EPI>), grid, dim3(256), 0, st, a);
   else hipLaunchKernelGGL((ffn_gemm_bf16<128, 128, 2, 2, KIND, EPI>), grid, dim3(256), 0, st, a);
 }
 
@@ -511,13 +886,18 @@ int check_ffn_shape(int dtype, int n_src, int G, int64_t C, int M, int H, int es
   const int Hl = H / n_esp;
   MOE_REQUIRE(M % 8 == 0 && Hl % 8 == 0, MOE_EUNSUPPORTED);
   MOE_REQUIRE((int64_t)n_src * C < (1ll << 31) && (int64_t)n_src * G * C < (1ll << 31), MOE_EUNSUPPORTED);
+  if (dtype == MOE_BF16) {  // 32-bit byte offsets inside one activation tensor / one expert's weight matrix
+    const uint64_t wide = (uint64_t)(M > Hl ? M : Hl);
+    MOE_REQUIRE((uint64_t)n_src * G * C * wide * 2 <= 0xFFFFFFF0ull, MOE_EUNSUPPORTED);
+    MOE_REQUIRE((uint64_t)M * H * 2 <= 0xFFFFFFF0ull, MOE_EUNSUPPORTED);
+  }
   return MOE_OK;
 }
 
 }  // namespace
 
 extern "C" int moe_ffn_set_tile(int tile) {
-  if (tile < 0 || tile > 2) return MOE_EINVAL;
+  if (tile < 0 || tile > 5) return MOE_EINVAL;
   g_tile_pref = tile;
   return MOE_OK;
 }

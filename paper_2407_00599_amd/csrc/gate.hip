@@ -22,7 +22,7 @@ namespace {
 
 using namespace moe;
 
-constexpr int GATE_TB = 256;  // tokens per block in gate_topk / gate_slots (one per thread)
+constexpr int GATE_TB = 64;   // tokens per block in gate_topk / gate_slots (one per thread)
 
 template <bool BF16>
 __device__ __forceinline__ void load8(const void* base, int64_t elem_off, bool ok, float* f) {

@@ -17,8 +17,9 @@ namespace {
 using namespace moe;
 
 constexpr int DX_TOK = 8;        // tokens per thread step in gate_dx
-constexpr int DX_TOK_BLK = 64;   // tokens per block in gate_dx
-constexpr int DWG_CHUNK = 256;   // tokens per partial sum in gate_dwg_partial
+constexpr int DX_TOK_BLK = 16;   // tokens per block in gate_dx
+// tokens per partial sum in gate_dwg_partial: at least 32, and at most 256 partial sums
+inline int dwg_chunk(int64_t S) { const int64_t c = (S + 255) / 256; return (int)(c < 32 ? 32 : c); }
 
 __global__ __launch_bounds__(256) void gate_dlogits(const float* __restrict__ dw, const float* __restrict__ w,
                                                     const int32_t* __restrict__ idx, const float* __restrict__ logits,
@@ -124,10 +125,11 @@ __global__ __launch_bounds__(128) void gate_dx(const float* __restrict__ dl, con
 // grid: (ceil(M/8/128), nchunk); partial[chunk][m][e] for m < M, plus row m = M for dbias.
 template <bool BF16>
 __global__ __launch_bounds__(128) void gate_dwg_partial(const void* __restrict__ x, const float* __restrict__ dl,
-                                                        float* __restrict__ partial, int64_t S, int M, int E) {
+                                                        float* __restrict__ partial, int64_t S, int M, int E,
+                                                        int chunk) {
   const int m0 = (blockIdx.x * 128 + threadIdx.x) * 8;
-  const int64_t tb = (int64_t)blockIdx.y * DWG_CHUNK;
-  const int64_t te = (tb + DWG_CHUNK < S) ? tb + DWG_CHUNK : S;
+  const int64_t tb = (int64_t)blockIdx.y * chunk;
+  const int64_t te = (tb + chunk < S) ? tb + chunk : S;
   float* out = partial + (int64_t)blockIdx.y * (M + 1) * E;
   if (m0 < M) {
     for (int e0 = 0; e0 < E; e0 += 16) {
@@ -177,7 +179,8 @@ __global__ __launch_bounds__(256) void gate_dwg_reduce(const float* __restrict__
 
 extern "C" size_t moe_gate_bwd_workspace_bytes(int64_t S, int M, int E) {
   if (S < 1 || M < 1 || E < 1) return 0;
-  const int64_t nchunk = (S + DWG_CHUNK - 1) / DWG_CHUNK;
+  const int chunk = dwg_chunk(S);
+  const int64_t nchunk = (S + chunk - 1) / chunk;
   return moe::align_up((size_t)nchunk * (size_t)(M + 1) * E * sizeof(float), 256);
 }
 
@@ -204,11 +207,12 @@ extern "C" int moe_gate_bwd(const float* dw, const float* w, const int32_t* idx,
   const dim3 grid_dx(gm, (unsigned)((S + DX_TOK_BLK - 1) / DX_TOK_BLK));
   if (bf) hipLaunchKernelGGL(gate_dx<true>, grid_dx, dim3(128), 0, st, dlogits, Wg, dx, S, M, E, dx_accumulate);
   else hipLaunchKernelGGL(gate_dx<false>, grid_dx, dim3(128), 0, st, dlogits, Wg, dx, S, M, E, dx_accumulate);
-  const int nchunk = (int)((S + DWG_CHUNK - 1) / DWG_CHUNK);
+  const int chunk = dwg_chunk(S);
+  const int nchunk = (int)((S + chunk - 1) / chunk);
   const dim3 grid_p(gm, (unsigned)nchunk);
   float* partial = (float*)ws;
-  if (bf) hipLaunchKernelGGL(gate_dwg_partial<true>, grid_p, dim3(128), 0, st, x, dlogits, partial, S, M, E);
-  else hipLaunchKernelGGL(gate_dwg_partial<false>, grid_p, dim3(128), 0, st, x, dlogits, partial, S, M, E);
+  if (bf) hipLaunchKernelGGL(gate_dwg_partial<true>, grid_p, dim3(128), 0, st, x, dlogits, partial, S, M, E, chunk);
+  else hipLaunchKernelGGL(gate_dwg_partial<false>, grid_p, dim3(128), 0, st, x, dlogits, partial, S, M, E, chunk);
   const int64_t n = (int64_t)(M + 1) * E;
   hipLaunchKernelGGL(gate_dwg_reduce, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, partial, nchunk, M, E, dWg,
                      dgate_bias);
