@@ -127,9 +127,11 @@ int moe_dispatch(const void* x, int dtype, int64_t S, int M, int E, int k, int64
 size_t moe_ffn_workspace_bytes(int dtype, int n_src, int G, int64_t C, int M, int H, int n_esp,
                                int backward);
 
-/* Tuning knob for the bf16 grouped GEMMs: 0 = choose the workgroup tile per GEMM from its
- * tile count (default), 1 = always 128x128, 2 = always 256x256.  Process-wide; affects speed
- * only, never results beyond fp32 summation order.  Returns MOE_EINVAL for other values. */
+/* Tuning knob for the bf16 grouped GEMMs.  0 = choose per GEMM from its tile count (default);
+ * 1 = 128x128 tiles, register-staged; 2 = 256x256 LDS-DMA kernel with 4 waves; 6 = the same
+ * with 8 waves (the default for all but tiny problems); 3, 4, 5 = 256x256 register-staged
+ * variants kept for comparison.  Process-wide; affects speed only, never results beyond fp32
+ * summation order.  Returns MOE_EINVAL for other values. */
 int moe_ffn_set_tile(int tile);
 
 int moe_expert_ffn_fwd(const void* X, int dtype, const void* W1, const void* W2,

@@ -202,6 +202,33 @@ __device__ __forceinline__ void store_tile(const GemmArgs& p, f32x16_t (&acc)[MB
   }
 }
 
+// Workgroup -> output tile.  Workgroup ids are dealt round-robin to the 8 XCDs, so id % 8 names
+// the XCD; each XCD is given one contiguous range of a linear tile order in which 32 consecutive
+// tiles (what its 32 CUs run at the same time) form an 8 (rows) x 4 (columns) patch of one expert:
+// per k step they share 8 + 4 operand slices in that XCD's L2 instead of 1 + 32.
+__device__ __forceinline__ bool map_tile(const GemmArgs& p, int& g, int& tm, int& tn) {
+  constexpr int SW = 4;
+  const int per_xcd = (p.total_tiles + 7) / 8;
+  const int tile = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
+  if (tile >= p.total_tiles) return false;
+  const int tiles_per_g = p.tiles_m * p.tiles_n;
+  g = tile / tiles_per_g;
+  const int t = tile - g * tiles_per_g;
+  const int full = p.tiles_n / SW;
+  const int strip = p.tiles_m * SW;
+  if (t < full * strip) {
+    const int sn = t / strip, r = t - sn * strip;
+    tm = r / SW;
+    tn = sn * SW + (r - tm * SW);
+  } else {
+    const int w = p.tiles_n - full * SW;
+    const int r = t - full * strip;
+    tm = r / w;
+    tn = full * SW + (r - tm * w);
+  }
+  return true;
+}
+
 // Instruction-order hints for the scheduler (sched_group_barrier): "N instructions of this
 // class next".  Recipe interleaves NM MFMAs with NA instructions of class MA and NB of class MB.
 enum { SG_MFMA = 0x008, SG_VMEM_READ = 0x020, SG_DS_READ = 0x100, SG_DS_WRITE = 0x200 };
@@ -236,14 +263,8 @@ __global__ __launch_bounds__(WM * WN * 64) void ffn_gemm_bf16(const GemmArgs p) 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm = wave / WN, wn = wave % WN;
 
-  // ---- tile assignment (XCD-contiguous remap) ----
-  const int per_xcd = (p.total_tiles + 7) / 8;
-  const int tile = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
-  if (tile >= p.total_tiles) return;
-  const int tiles_per_g = p.tiles_m * p.tiles_n;
-  const int g = tile / tiles_per_g;
-  const int tr = tile - g * tiles_per_g;
-  const int tm = tr / p.tiles_n, tn = tr - tm * p.tiles_n;
+  int g, tm, tn;
+  if (!map_tile(p, g, tm, tn)) return;
   const int m0 = tm * TM, n0 = tn * TN;
 
   const int64_t b_base = (int64_t)g * p.b_goff + p.b_off;   // weight-type B: start of expert g's slice
@@ -481,6 +502,99 @@ __global__ __launch_bounds__(WM * WN * 64) void ffn_gemm_bf16(const GemmArgs p) 
   store_tile<MB, NBK, KIND, EPI>(p, acc, g, m0 + wm * TMW, n0 + wn * TNW, lane);
 }
 
+// Epilogue of the DMA kernel, staged through LDS so that global memory sees 16-byte accesses in
+// which consecutive lanes cover a contiguous run of a row (the MFMA result layout alone gives
+// 8-byte pieces strided across 32 rows).  Each wave owns a private slice of the (now idle) stage
+// memory: per 32-row block it writes bf16 results in [32][CW] row-major form (CW = columns of the
+// wave tile, row pitch 2 CW + 16 bytes), reads them back row-wise and stores them; the GeLU
+// epilogues stage their second output, and the saved pre-activation they read, the same way.
+template <int KIND, int EPI, int NBK>
+__device__ __forceinline__ void store_tile_lds(const GemmArgs& p, f32x16_t (&acc)[4][NBK], char* wave_lds, int g,
+                                               int mbase, int nbase, int lane) {
+  constexpr int CW = 32 * NBK;            // columns of the wave tile
+  constexpr int PITCH_B = 2 * CW + 16;    // staged row pitch, bytes
+  constexpr int BUF = 32 * PITCH_B;
+  constexpr int LPR = CW / 8;             // lanes per row in the row-wise phase (16 bytes each)
+  constexpr int RPI = 64 / LPR;           // rows per instruction
+  constexpr int NT_ = 32 / RPI;           // instructions per 32-row block
+  bf16_t* __restrict__ Cb = reinterpret_cast<bf16_t*>(p.C);
+  bf16_t* __restrict__ C2b = reinterpret_cast<bf16_t*>(p.C2);
+  const bf16_t* __restrict__ Zb = reinterpret_cast<const bf16_t*>(p.Zin);
+  char* buf0 = wave_lds;          // first output (or staged Z on the way in)
+  char* buf1 = wave_lds + BUF;    // second output
+  const int rl = lane / LPR;      // row-wise phase: row RPI t + rl, 16-byte chunk lane % LPR
+  const int cc = lane % LPR;
+  const int ncol = nbase + cc * 8;
+  const bool col_ok = ncol < p.Ndim;
+  // accumulator phase: row lane % 32, for block j and q4: 4 columns at 32 j + 8 q4 + 4 (lane / 32)
+  const int acc_off = (lane & 31) * PITCH_B + (lane >> 5) * 8;
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    int64_t crow[NT_];  // global row offsets of the rows this lane touches in the row-wise phase
+    bool row_ok[NT_];
+#pragma unroll
+    for (int t = 0; t < NT_; ++t) {
+      const int m = mbase + i * 32 + RPI * t + rl;
+      row_ok[t] = m < p.Mdim;
+      const int mm = row_ok[t] ? m : 0;
+      if (KIND == KIND_TN) crow[t] = (int64_t)g * p.c_goff + p.c_off + (int64_t)mm * p.ldc;
+      else crow[t] = phys_row(mm, g, p.G, p.Cc) * p.ldc;
+    }
+    if (EPI == EPI_DGELU) {  // bring in the saved pre-activation, row-wise
+#pragma unroll
+      for (int t = 0; t < NT_; ++t) {
+        uint4 z = make_uint4(0, 0, 0, 0);
+        if (row_ok[t] && col_ok) z = *reinterpret_cast<const uint4*>(Zb + crow[t] + ncol);
+        *reinterpret_cast<uint4*>(buf0 + (RPI * t + rl) * PITCH_B + cc * 16) = z;
+      }
+    }
+#pragma unroll
+    for (int j = 0; j < NBK; ++j) {
+#pragma unroll
+      for (int q4 = 0; q4 < 4; ++q4) {
+        const float v[4] = {acc[i][j][q4 * 4 + 0], acc[i][j][q4 * 4 + 1], acc[i][j][q4 * 4 + 2], acc[i][j][q4 * 4 + 3]};
+        char* a0 = buf0 + acc_off + j * 64 + q4 * 16;
+        char* a1 = buf1 + acc_off + j * 64 + q4 * 16;
+        if (EPI == EPI_STORE) {
+          *reinterpret_cast<uint2*>(a0) = make_uint2(pack_bf16x2(v[0], v[1]), pack_bf16x2(v[2], v[3]));
+        } else if (EPI == EPI_GELU) {
+          float a[4];
+#pragma unroll
+          for (int e = 0; e < 4; ++e) {
+            float dg;
+            gelu_fast(v[e], a[e], dg);
+          }
+          *reinterpret_cast<uint2*>(a0) = make_uint2(pack_bf16x2(v[0], v[1]), pack_bf16x2(v[2], v[3]));
+          *reinterpret_cast<uint2*>(a1) = make_uint2(pack_bf16x2(a[0], a[1]), pack_bf16x2(a[2], a[3]));
+        } else {
+          const uint2 zq = *reinterpret_cast<const uint2*>(a0);
+          const float z[4] = {__uint_as_float(zq.x << 16), __uint_as_float(zq.x & 0xFFFF0000u),
+                              __uint_as_float(zq.y << 16), __uint_as_float(zq.y & 0xFFFF0000u)};
+          float a[4], d[4];
+#pragma unroll
+          for (int e = 0; e < 4; ++e) {
+            float dg;
+            gelu_fast(z[e], a[e], dg);
+            d[e] = v[e] * dg;
+          }
+          *reinterpret_cast<uint2*>(a0) = make_uint2(pack_bf16x2(d[0], d[1]), pack_bf16x2(d[2], d[3]));
+          *reinterpret_cast<uint2*>(a1) = make_uint2(pack_bf16x2(a[0], a[1]), pack_bf16x2(a[2], a[3]));
+        }
+      }
+    }
+    // row-wise read-back and store (LDS operations of one wave complete in program order)
+#pragma unroll
+    for (int t = 0; t < NT_; ++t) {
+      const uint4 o0 = *reinterpret_cast<const uint4*>(buf0 + (RPI * t + rl) * PITCH_B + cc * 16);
+      if (row_ok[t] && col_ok) *reinterpret_cast<uint4*>(Cb + crow[t] + ncol) = o0;
+      if (EPI != EPI_STORE) {
+        const uint4 o1 = *reinterpret_cast<const uint4*>(buf1 + (RPI * t + rl) * PITCH_B + cc * 16);
+        if (row_ok[t] && col_ok) *reinterpret_cast<uint4*>(C2b + crow[t] + ncol) = o1;
+      }
+    }
+  }
+}
+
 // ------------------------------------------------------------------------------------------
 // bf16 MFMA kernel with an LDS-DMA pipeline (the fast path for large GEMMs).
 //
@@ -493,7 +607,7 @@ __global__ __launch_bounds__(WM * WN * 64) void ffn_gemm_bf16(const GemmArgs p) 
 //   operand with k contiguous in memory : stage holds [row][32 k] (64 B rows, 4 chunks), chunk c
 //       of row r sits in slot c ^ ((r >> 2) & 3); fragments are read with ds_read_b128.
 //   operand with k as the slow index    : stage holds [32 k][256 cols] (512 B rows, 32 chunks),
-//       chunk c of k-row k sits in slot c ^ (2 (k & 3)); fragments are read with the transposing
+//       chunk c of k-row k sits in slot c ^ (4 (k & 3)); fragments are read with the transposing
 //       LDS load ds_read_b64_tr_b16: a 16-lane group reads a 4(k) x 16(col) patch (lane s: k-row
 //       s/4, 8-byte piece s%4) and lane i receives the 4 k-values of column i.
 // Pipeline: tile t+3 is requested while tile t is multiplied.  Once per k tile, between its two
@@ -534,24 +648,22 @@ __device__ __forceinline__ void lds_read_nc(Frag& f, uint32_t addr_lo, uint32_t 
 }
 __device__ __forceinline__ void ready(Frag& f) { asm volatile("" : "+v"(f.q)); }
 
-template <int KIND, int EPI>
-__global__ __launch_bounds__(256) void ffn_gemm_dma(const GemmArgs p) {
+// WN = waves along n: 2 (4 waves, 128x128 per wave) or 4 (8 waves, 128x64 per wave, two per SIMD)
+template <int KIND, int EPI, int WN>
+__global__ __launch_bounds__(128 * WN) void ffn_gemm_dma(const GemmArgs p) {
   constexpr bool A_NC = (KIND == KIND_TN);                     // A has k as the slow index
   constexpr bool B_NC = (KIND == KIND_NN || KIND == KIND_TN);  // B has k as the slow index
-  constexpr int MB = 4, NBK = 4;
+  constexpr int MB = 4, NBK = 8 / WN;     // 32x32 blocks per wave tile
+  constexpr int RPW = 8 / WN;             // requests per wave per operand per k tile (16 in all)
 
   __shared__ __attribute__((aligned(1024))) char smem[DSTAGES * DSTAGE];
 
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int wm = wave >> 1, wn = wave & 1;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // uniform: keeps LDS bases in SGPRs
+  const int wm = wave / WN, wn = wave % WN;
 
-  const int per_xcd = (p.total_tiles + 7) / 8;
-  const int tile = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
-  if (tile >= p.total_tiles) return;
-  const int tiles_per_g = p.tiles_m * p.tiles_n;
-  const int g = tile / tiles_per_g;
-  const int tr = tile - g * tiles_per_g;
-  const int tm = tr / p.tiles_n, tn = tr - tm * p.tiles_n;
+  int g, tm, tn;
+  if (!map_tile(p, g, tm, tn)) return;
   const int m0 = tm * DT, n0 = tn * DT;
 
   const int64_t b_base = (int64_t)g * p.b_goff + p.b_off;
@@ -564,22 +676,22 @@ __global__ __launch_bounds__(256) void ffn_gemm_dma(const GemmArgs p) {
   const int kpc = (p.Cc + DK - 1) / DK;  // TN: k tiles per chunk
   const int nk = (KIND == KIND_TN) ? p.n_src * kpc : (p.Kdim + DK - 1) / DK;
 
-  // ---- per-lane request coordinates: each wave issues 4 requests per operand per k tile ----
-  // k-contiguous operand, request q = 4 wave + j: rows 16 q + lane/4, slot lane%4 holds logical chunk kc_c
+  // ---- per-lane request coordinates: each wave issues RPW requests per operand per k tile ----
+  // k-contiguous operand, request q = RPW wave + j: rows 16 q + lane/4, slot lane%4 holds logical chunk kc_c
   const int kc_c = (lane & 3) ^ ((lane >> 4) & 3);
   // k-slow operand, request q: k-rows 2 q + lane/32, slot lane%32 holds logical chunk nc_c[j]
-  uint32_t a_req[4], b_req[4];   // byte offset of the lane's 16 bytes at k tile 0, or OOB
-  int a_k[4], b_k[4];            // k index (within the k tile) this request covers (k-slow), or first k (k-contig)
+  uint32_t a_req[RPW], b_req[RPW];   // byte offset of the lane's 16 bytes at k tile 0, or OOB
+  int a_k[RPW], b_k[RPW];            // k index (within the k tile) this request covers (k-slow), or first k (k-contig)
 #pragma unroll
-  for (int j = 0; j < 4; ++j) {
-    const int q = wave * 4 + j;
+  for (int j = 0; j < RPW; ++j) {
+    const int q = wave * RPW + j;
     if (!A_NC) {
       const int r = m0 + q * 16 + (lane >> 2);
       a_k[j] = kc_c * 8;
       a_req[j] = (r < p.Mdim) ? (uint32_t)((phys_row(r, g, p.G, p.Cc) * p.lda + kc_c * 8) * 2) : OOB;
     } else {
       const int k = 2 * q + (lane >> 5);
-      const int col = m0 + (((lane & 31) ^ (2 * (k & 3))) * 8);
+      const int col = m0 + (((lane & 31) ^ (4 * (k & 3))) * 8);
       a_k[j] = k;
       a_req[j] = (col < p.Mdim) ? (uint32_t)(((int64_t)k * p.lda + col) * 2) : OOB;
     }
@@ -589,101 +701,113 @@ __global__ __launch_bounds__(256) void ffn_gemm_dma(const GemmArgs p) {
       b_req[j] = (n < p.Ndim) ? (uint32_t)(((int64_t)n * p.ldb + kc_c * 8) * 2) : OOB;
     } else {
       const int k = 2 * q + (lane >> 5);
-      const int col = n0 + (((lane & 31) ^ (2 * (k & 3))) * 8);
+      const int col = n0 + (((lane & 31) ^ (4 * (k & 3))) * 8);
       b_k[j] = k;
       b_req[j] = (col < p.Ndim) ? (uint32_t)(((int64_t)k * p.ldb + col) * 2) : OOB;
     }
   }
 
-  // requests of k tile kt into its stage; tiles past the end still issue (all lanes out of range)
-  // so that the number of outstanding requests per wave is the same in every iteration
-  auto request = [&](int kt) {
+  // Requests of k tile kt into its stage, one instruction (1 KiB) at a time: which = 0 (A) / 1 (B),
+  // j = 0..RPW-1.  Tiles past the end still issue (all lanes out of range, zeros are written) so that
+  // the number of outstanding requests per wave is the same in every iteration.
+  auto request1 = [&](int kt, int which, int j) {
     char* st = smem + (kt & (DSTAGES - 1)) * DSTAGE;
     const bool live = kt < nk;
-    uint32_t a_add, b_add;   // byte offset of the k tile
-    int a_lim, b_lim;        // valid k count in this tile
+    uint32_t add;   // byte offset of the k tile
+    int lim;        // valid k count in this tile
     if (KIND == KIND_TN) {
       const int s = kt / kpc;
       const int c0 = (kt - s * kpc) * DK;
       const int64_t row0 = ((int64_t)s * p.G + g) * p.Cc + c0;
-      a_add = (uint32_t)(row0 * p.lda * 2);
-      b_add = (uint32_t)(row0 * p.ldb * 2);
-      a_lim = b_lim = live ? p.Cc - c0 : 0;
+      add = (uint32_t)(row0 * (which ? p.ldb : p.lda) * 2);
+      lim = live ? p.Cc - c0 : 0;
     } else {
-      a_add = (uint32_t)kt * (DK * 2);
-      b_add = B_NC ? (uint32_t)((int64_t)kt * DK * p.ldb * 2) : (uint32_t)kt * (DK * 2);
-      a_lim = b_lim = live ? p.Kdim - kt * DK : 0;
+      add = (which && B_NC) ? (uint32_t)((int64_t)kt * DK * p.ldb * 2) : (uint32_t)kt * (DK * 2);
+      lim = live ? p.Kdim - kt * DK : 0;
     }
-#pragma unroll
-    for (int j = 0; j < 4; ++j) {
-      const int q = wave * 4 + j;
-      dma16(rA, reinterpret_cast<bf16_t*>(st + q * 1024), (a_req[j] != OOB && a_k[j] < a_lim) ? a_req[j] + a_add : OOB);
-    }
-#pragma unroll
-    for (int j = 0; j < 4; ++j) {
-      const int q = wave * 4 + j;
+    const int q = wave * RPW + j;
+    if (which == 0)
+      dma16(rA, reinterpret_cast<bf16_t*>(st + q * 1024), (a_req[j] != OOB && a_k[j] < lim) ? a_req[j] + add : OOB);
+    else
       dma16(rB, reinterpret_cast<bf16_t*>(st + DREGION + q * 1024),
-            (b_req[j] != OOB && b_k[j] < b_lim) ? b_req[j] + b_add : OOB);
-    }
+            (b_req[j] != OOB && b_k[j] < lim) ? b_req[j] + add : OOB);
+  };
+  auto request_half = [&](int kt, int which) {
+#pragma unroll
+    for (int j = 0; j < RPW; ++j) request1(kt, which, j);
   };
 
   // ---- per-lane fragment addresses inside a stage (bytes), for k step kk = 0; kk = 1 adds a constant ----
   // k-contiguous: row = base + 32 i + lane%32, logical chunk 2 kk + lane/32  -> slot ^ ((row >> 2) & 3)
   // k-slow: 16-lane group b = lane/16, s = lane%16: k = 16 kk + 8 (b/2) + 4 h + s/4,
   //         col = base + 32 j + 16 (b%2) + 4 (s%4); chunk = col/8 ^ 2 (s/4), piece = (s%4)&1
-  // k-contiguous: a_fr[kk][0]; k-slow: a_fr[h][parity of the 32-column block] (the swizzle touches the
-  // chunk-index bit that an odd block offset sets, so odd blocks get their own base address)
-  uint32_t a_fr[2][2], b_fr[2][2];
+  // k-contiguous: x_fr[kk][0] (blocks add a constant); k-slow: x_fr[h][block] (the swizzle touches the
+  // chunk-index bits that the block offset sets, so every 32-column block has its own base address)
+  uint32_t a_fr[2][4], b_fr[2][NBK];
   {
     const int b = lane >> 4, s = lane & 15;
     if (!A_NC) {
       const int row = wm * 128 + (lane & 31);
       for (int kk = 0; kk < 2; ++kk)
-        a_fr[kk][0] = a_fr[kk][1] = row * 64 + (((2 * kk + (lane >> 5)) ^ ((lane >> 2) & 3)) * 16);
+        a_fr[kk][0] = a_fr[kk][1] = a_fr[kk][2] = a_fr[kk][3] =
+            row * 64 + (((2 * kk + (lane >> 5)) ^ ((lane >> 2) & 3)) * 16);
     } else {
       for (int h = 0; h < 2; ++h)
-        for (int par = 0; par < 2; ++par) {
-          const int col = wm * 128 + 32 * par + 16 * (b & 1) + 4 * (s & 3);
+        for (int blk = 0; blk < 4; ++blk) {
+          const int col = wm * 128 + 32 * blk + 16 * (b & 1) + 4 * (s & 3);
           const int k = 8 * (b >> 1) + 4 * h + (s >> 2);
-          a_fr[h][par] = k * 512 + (((col >> 3) ^ (2 * (s >> 2))) * 16) + ((s & 1) * 8);
+          a_fr[h][blk] = k * 512 + (((col >> 3) ^ (4 * (s >> 2))) * 16) + ((s & 1) * 8);
         }
     }
     if (!B_NC) {
-      const int row = wn * 128 + (lane & 31);
+      const int row = wn * (32 * NBK) + (lane & 31);
       for (int kk = 0; kk < 2; ++kk)
-        b_fr[kk][0] = b_fr[kk][1] = DREGION + row * 64 + (((2 * kk + (lane >> 5)) ^ ((lane >> 2) & 3)) * 16);
+        for (int blk = 0; blk < NBK; ++blk)
+          b_fr[kk][blk] = DREGION + row * 64 + (((2 * kk + (lane >> 5)) ^ ((lane >> 2) & 3)) * 16);
     } else {
       for (int h = 0; h < 2; ++h)
-        for (int par = 0; par < 2; ++par) {
-          const int col = wn * 128 + 32 * par + 16 * (b & 1) + 4 * (s & 3);
+        for (int blk = 0; blk < NBK; ++blk) {
+          const int col = wn * (32 * NBK) + 32 * blk + 16 * (b & 1) + 4 * (s & 3);
           const int k = 8 * (b >> 1) + 4 * h + (s >> 2);
-          b_fr[h][par] = DREGION + k * 512 + (((col >> 3) ^ (2 * (s >> 2))) * 16) + ((s & 1) * 8);
+          b_fr[h][blk] = DREGION + k * 512 + (((col >> 3) ^ (4 * (s >> 2))) * 16) + ((s & 1) * 8);
         }
     }
   }
   Frag fa[2][MB], fb[2][NBK];
   const uint32_t lds0 = (uint32_t)(uintptr_t)(LDS_AS char*)smem;
-  // set = kk: fragments of k step kk of tile kt
-  auto load_frags = [&](int kt, auto kk_tag) {
+  // fragments of k step kk of tile kt go to register set kk; part 0 = the four B fragments,
+  // part 1 = A fragments 0,1, part 2 = A fragments 2,3 (so the reads can be spread between MFMAs)
+  auto load_frags = [&](int kt, auto kk_tag, int part) {
     constexpr int kk = decltype(kk_tag)::value;
     const uint32_t st = lds0 + (uint32_t)(kt & (DSTAGES - 1)) * DSTAGE;
-    if (!A_NC) {
-      lds_read_kc<0 * 2048>(fa[kk][0], st + a_fr[kk][0]); lds_read_kc<1 * 2048>(fa[kk][1], st + a_fr[kk][0]);
-      lds_read_kc<2 * 2048>(fa[kk][2], st + a_fr[kk][0]); lds_read_kc<3 * 2048>(fa[kk][3], st + a_fr[kk][0]);
+    if (part == 0) {
+      if (!B_NC) {
+        lds_read_kc<0 * 2048>(fb[kk][0], st + b_fr[kk][0]); lds_read_kc<1 * 2048>(fb[kk][1], st + b_fr[kk][0]);
+        if (NBK == 4) {
+          lds_read_kc<2 * 2048>(fb[kk][NBK - 2], st + b_fr[kk][0]); lds_read_kc<3 * 2048>(fb[kk][NBK - 1], st + b_fr[kk][0]);
+        }
+      } else {
+        lds_read_nc<kk * 8192>(fb[kk][0], st + b_fr[0][0], st + b_fr[1][0]);
+        lds_read_nc<kk * 8192>(fb[kk][1], st + b_fr[0][1], st + b_fr[1][1]);
+        if (NBK == 4) {
+          lds_read_nc<kk * 8192>(fb[kk][NBK - 2], st + b_fr[0][NBK - 2], st + b_fr[1][NBK - 2]);
+          lds_read_nc<kk * 8192>(fb[kk][NBK - 1], st + b_fr[0][NBK - 1], st + b_fr[1][NBK - 1]);
+        }
+      }
+    } else if (part == 1) {
+      if (!A_NC) {
+        lds_read_kc<0 * 2048>(fa[kk][0], st + a_fr[kk][0]); lds_read_kc<1 * 2048>(fa[kk][1], st + a_fr[kk][0]);
+      } else {
+        lds_read_nc<kk * 8192>(fa[kk][0], st + a_fr[0][0], st + a_fr[1][0]);
+        lds_read_nc<kk * 8192>(fa[kk][1], st + a_fr[0][1], st + a_fr[1][1]);
+      }
     } else {
-      lds_read_nc<kk * 8192 + 0>(fa[kk][0], st + a_fr[0][0], st + a_fr[1][0]);
-      lds_read_nc<kk * 8192 + 0>(fa[kk][1], st + a_fr[0][1], st + a_fr[1][1]);
-      lds_read_nc<kk * 8192 + 128>(fa[kk][2], st + a_fr[0][0], st + a_fr[1][0]);
-      lds_read_nc<kk * 8192 + 128>(fa[kk][3], st + a_fr[0][1], st + a_fr[1][1]);
-    }
-    if (!B_NC) {
-      lds_read_kc<0 * 2048>(fb[kk][0], st + b_fr[kk][0]); lds_read_kc<1 * 2048>(fb[kk][1], st + b_fr[kk][0]);
-      lds_read_kc<2 * 2048>(fb[kk][2], st + b_fr[kk][0]); lds_read_kc<3 * 2048>(fb[kk][3], st + b_fr[kk][0]);
-    } else {
-      lds_read_nc<kk * 8192 + 0>(fb[kk][0], st + b_fr[0][0], st + b_fr[1][0]);
-      lds_read_nc<kk * 8192 + 0>(fb[kk][1], st + b_fr[0][1], st + b_fr[1][1]);
-      lds_read_nc<kk * 8192 + 128>(fb[kk][2], st + b_fr[0][0], st + b_fr[1][0]);
-      lds_read_nc<kk * 8192 + 128>(fb[kk][3], st + b_fr[0][1], st + b_fr[1][1]);
+      if (!A_NC) {
+        lds_read_kc<2 * 2048>(fa[kk][2], st + a_fr[kk][0]); lds_read_kc<3 * 2048>(fa[kk][3], st + a_fr[kk][0]);
+      } else {
+        lds_read_nc<kk * 8192>(fa[kk][2], st + a_fr[0][2], st + a_fr[1][2]);
+        lds_read_nc<kk * 8192>(fa[kk][3], st + a_fr[0][3], st + a_fr[1][3]);
+      }
     }
   };
   auto frags_ready = [&](int set) {
@@ -704,49 +828,57 @@ __global__ __launch_bounds__(256) void ffn_gemm_dma(const GemmArgs p) {
 #pragma unroll
       for (int q = 0; q < 16; ++q) acc[i][j][q] = 0.f;
 
-  request(0);
-  request(1);
-  request(2);
-  __builtin_amdgcn_s_waitcnt(0x4F70);  // vmcnt(16): this wave's requests for tile 0 have landed
+  request_half(0, 0); request_half(0, 1);
+  request_half(1, 0); request_half(1, 1);
+  request_half(2, 0);
+  // vmcnt(3 RPW): this wave's requests for tile 0 have landed
+  __builtin_amdgcn_s_waitcnt(RPW == 4 ? 0x0F7C : 0x0F76);
   __builtin_amdgcn_s_barrier();
-  load_frags(0, K0{});
+  load_frags(0, K0{}, 0); load_frags(0, K0{}, 1); load_frags(0, K0{}, 2);
 
-  auto mfma_rows = [&](int set, int i_begin, int i_end) {
+  auto mfma_row = [&](int set, int i) {
 #pragma unroll
-    for (int i = 0; i < MB; ++i) {
-      if (i < i_begin || i >= i_end) continue;
-#pragma unroll
-      for (int j = 0; j < NBK; ++j)
-        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[set][j].v, fa[set][i].v, acc[i][j], 0, 0, 0);
-    }
+    for (int j = 0; j < NBK; ++j)
+      acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[set][j].v, fa[set][i].v, acc[i][j], 0, 0, 0);
   };
+  // Each k tile is two MFMA steps of four rows (NBK MFMAs each).  Between the rows go, one piece at
+  // a time, the fragment reads of the next step and the tile requests, so that neither the LDS nor
+  // the address path sees a burst and the matrix pipe always has work queued.
+  //   step 0: B-operand requests of tile kt+2;  step 1: barrier, then A-operand requests of tile kt+3
   for (int kt = 0; kt < nk; ++kt) {
-    // ---- first k step of tile kt; its fragments were requested half a tile ago ----
     frags_ready(0);
     __builtin_amdgcn_sched_barrier(0);
-    mfma_rows(0, 0, 1);                  // a few MFMAs first, so the reads below issue in their shadow
-    __builtin_amdgcn_sched_barrier(0);
-    load_frags(kt, K1{});
-    __builtin_amdgcn_sched_barrier(0);
-    mfma_rows(0, 1, MB);
-    __builtin_amdgcn_sched_barrier(0);
-    // ---- second k step; in its shadow: barrier, first fragments of tile kt+1, requests of tile kt+3 ----
+#pragma unroll
+    for (int i = 0; i < MB; ++i) {
+      mfma_row(0, i);
+      __builtin_amdgcn_sched_barrier(0);
+      if (i < 3) load_frags(kt, K1{}, i);
+      if (i < RPW) request1(kt + 2, 1, i);
+      __builtin_amdgcn_sched_barrier(0);
+    }
     frags_ready(1);
     __builtin_amdgcn_sched_barrier(0);
-    mfma_rows(1, 0, 1);
+    mfma_row(1, 0);
     __builtin_amdgcn_sched_barrier(0);
-    __builtin_amdgcn_s_waitcnt(0x0F78);  // vmcnt(8): tile kt+1 has landed (tile kt+2 may be in flight)
+    // vmcnt(2 RPW): tile kt+1 has landed (the requests of tile kt+2 may still be in flight)
+    __builtin_amdgcn_s_waitcnt(RPW == 4 ? 0x0F78 : 0x0F74);
     __builtin_amdgcn_s_barrier();        // everyone is past tile kt-1, and tile kt+1 is complete
     __builtin_amdgcn_sched_barrier(0);
-    load_frags(kt + 1, K0{});
-    __builtin_amdgcn_sched_barrier(0);
-    request(kt + 3);                     // refills the stage of tile kt-1
-    mfma_rows(1, 1, MB);
-    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int i = 1; i < MB; ++i) {
+      load_frags(kt + 1, K0{}, i - 1);
+      if (i - 1 < RPW) request1(kt + 3, 0, i - 1);
+      __builtin_amdgcn_sched_barrier(0);
+      mfma_row(1, i);
+      __builtin_amdgcn_sched_barrier(0);
+    }
+    if (RPW == 4) request1(kt + 3, 0, 3);
   }
   __builtin_amdgcn_s_waitcnt(0x0070);  // drain trailing (empty) requests and fragment reads before LDS is released
 
-  store_tile<MB, NBK, KIND, EPI>(p, acc, g, m0 + wm * 128, n0 + wn * 128, lane);
+  __syncthreads();  // every wave is done reading fragments: the stage memory can be reused
+  store_tile_lds<KIND, EPI, NBK>(p, acc, smem + wave * (DSTAGES * DSTAGE / (2 * WN)), g, m0 + wm * 128,
+                                 n0 + wn * (32 * NBK), lane);
 }
 
 // ------------------------------------------------------------------------------------------
@@ -863,7 +995,7 @@ void launch_gemm(GemmArgs a, int dtype, hipStream_t st) {
   a.a_bytes = act_rows * (uint64_t)a.lda * 2;
   a.b_bytes = (KIND == KIND_TN) ? act_rows * (uint64_t)a.ldb * 2 : (uint64_t)a.G * (uint64_t)a.b_goff * 2;
   const int64_t big_tiles = (int64_t)a.G * ((a.Mdim + 255) / 256) * ((a.Ndim + 255) / 256);
-  bool big = big_tiles >= 512;
+  bool big = big_tiles >= 64;
   if (g_tile_pref == 1) big = false;
   if (g_tile_pref >= 2) big = true;
   const int T = big ? 256 : 128;
@@ -871,8 +1003,10 @@ void launch_gemm(GemmArgs a, int dtype, hipStream_t st) {
   a.tiles_n = (a.Ndim + T - 1) / T;
   a.total_tiles = a.G * a.tiles_m * a.tiles_n;
   const dim3 grid((unsigned)(((a.total_tiles + 7) / 8) * 8));
-  if (big && g_tile_pref != 3 && g_tile_pref != 4 && g_tile_pref != 5)
-    hipLaunchKernelGGL((ffn_gemm_dma<KIND, EPI>), grid, dim3(256), 0, st, a);
+  if (big && (g_tile_pref == 0 || g_tile_pref == 6))
+    hipLaunchKernelGGL((ffn_gemm_dma<KIND, EPI, 4>), grid, dim3(512), 0, st, a);
+  else if (big && g_tile_pref == 2)
+    hipLaunchKernelGGL((ffn_gemm_dma<KIND, EPI, 2>), grid, dim3(256), 0, st, a);
   else if (big && g_tile_pref == 3) hipLaunchKernelGGL((ffn_gemm_bf16<256, 256, 2, 4, KIND, EPI>), grid, dim3(512), 0, st, a);
   else if (big && g_tile_pref == 4) hipLaunchKernelGGL((ffn_gemm_bf16<256, 256, 4, 2, KIND, EPI>), grid, dim3(512), 0, st, a);
   else if (big) hipLaunchKernelGGL((ffn_gemm_bf16<256, 256, 2, 2, KIND, EPI>), grid, dim3(256), 0, st, a);
@@ -897,7 +1031,7 @@ int check_ffn_shape(int dtype, int n_src, int G, int64_t C, int M, int H, int es
 }  // namespace
 
 extern "C" int moe_ffn_set_tile(int tile) {
-  if (tile < 0 || tile > 5) return MOE_EINVAL;
+  if (tile < 0 || tile > 6) return MOE_EINVAL;
   g_tile_pref = tile;
   return MOE_OK;
 }

@@ -36,6 +36,10 @@ CASES = [
     (3, 2, 150, 256, 512, 2, 1, "bf16", 1),
     (1, 2, 300, 512, 768, 1, 0, "bf16", 2),
     (2, 3, 200, 264, 1040, 2, 0, "bf16", 2),
+    (1, 2, 300, 512, 768, 1, 0, "bf16", 6),
+    (2, 3, 200, 264, 1040, 2, 0, "bf16", 6),
+    (3, 2, 77, 136, 520, 1, 0, "bf16", 6),
+    (2, 2, 150, 256, 512, 2, 1, "bf16", 5),
     (4, 2, 70, 136, 520, 1, 0, "bf16", 1),
     (1, 1, 1, 8, 8, 1, 0, "bf16", 1),
     (5, 1, 64, 1024, 64, 4, 3, "bf16", 0),
