@@ -20,6 +20,9 @@ sys.path.insert(0, ROOT)
 
 MFMA_BF16_PEAK_TFLOPS = 2500.0   # MI355X dense bf16 matrix peak
 HBM_PEAK_GBS = 8000.0
+# HBM bytes per GEMM launch (mean of the 6 launches), from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of
+# this command scaled by the copy calibration; None where no such run has been made (see profiles/).
+MEASURED_TRAFFIC = {}
 
 
 def main():
@@ -29,7 +32,10 @@ def main():
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--config", default="layer_bf16", help="workload name from synth.CONFIGS")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--tile", type=int, default=0, help="FFN GEMM tile: 0 auto, 1 = 128x128, 2 = 256x256")
+    ap.add_argument("--tile", type=int, default=0, help="FFN GEMM variant, see moe_ffn_set_tile (0 = auto)")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run a plain 1 GiB device-to-device copy 5 times (known traffic, used to scale the "
+                         "FETCH_SIZE / WRITE_SIZE counters when the run is profiled with rocprofv3 --pmc)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures one rank on one GPU: this build has no inter-GPU collectives, "
@@ -88,6 +94,13 @@ def main():
         for t in (L.Yret, L.dbuf):
             t.copy_((torch.randn(t.shape, generator=gen, device=dev, dtype=torch.float32) * 0.5).to(tdt))
 
+    if args.calibrate_copy:
+        src = torch.ones(1 << 28, dtype=torch.float32, device=dev); dst = torch.empty_like(src)
+        for _ in range(5):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
+
     names = MoERankShape.STEPS
     for _ in range(args.warmup):
         L.step()
@@ -114,8 +127,8 @@ def main():
     gemm_ms = (per_call["ffn_fwd"] + per_call["ffn_bwd"]) / 6.0
     achieved = flops_per_launch / (gemm_ms * 1e-3) / 1e12
     roofline = {"bound": "mfma", "achieved": round(achieved, 2), "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
-                "frac": round(achieved / MFMA_BF16_PEAK_TFLOPS, 4), "traffic": None,
-                "kernel": "ffn_gemm_bf16 (6 launches per step)", "launch_ms": round(gemm_ms, 4),
+                "frac": round(achieved / MFMA_BF16_PEAK_TFLOPS, 4), "traffic": MEASURED_TRAFFIC.get(cfg.name),
+                "kernel": "ffn_gemm_dma (6 launches per step)", "launch_ms": round(gemm_ms, 4),
                 "flops_per_launch": flops_per_launch}
     if cfg.dtype == "f32":
         roofline.update({"bound": "alu", "peak": 78.6, "frac": round(achieved / 78.6, 5),

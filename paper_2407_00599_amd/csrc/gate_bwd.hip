@@ -17,7 +17,7 @@ namespace {
 using namespace moe;
 
 constexpr int DX_TOK = 8;        // tokens per thread step in gate_dx
-constexpr int DX_TOK_BLK = 16;   // tokens per block in gate_dx
+constexpr int DX_TOK_BLK = 8;    // tokens per block in gate_dx
 // tokens per partial sum in gate_dwg_partial: at least 32, and at most 256 partial sums
 inline int dwg_chunk(int64_t S) { const int64_t c = (S + 255) / 256; return (int)(c < 32 ? 32 : c); }
 
@@ -138,6 +138,7 @@ __global__ __launch_bounds__(128) void gate_dwg_partial(const void* __restrict__
       for (int q = 0; q < 8; ++q)
 #pragma unroll
         for (int e = 0; e < 16; ++e) acc[q][e] = 0.f;
+#pragma unroll 4
       for (int64_t t = tb; t < te; ++t) {
         float xf[8];
         ld8g<BF16>(x, t * (int64_t)M + m0, xf);
@@ -164,15 +165,22 @@ __global__ __launch_bounds__(128) void gate_dwg_partial(const void* __restrict__
   }
 }
 
-__global__ __launch_bounds__(256) void gate_dwg_reduce(const float* __restrict__ partial, int nchunk, int M, int E,
-                                                       float* __restrict__ dWg, float* __restrict__ dbias) {
+__global__ __launch_bounds__(64) void gate_dwg_reduce(const float* __restrict__ partial, int nchunk, int M, int E,
+                                                      float* __restrict__ dWg, float* __restrict__ dbias) {
   const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   const int64_t n = (int64_t)(M + 1) * E;
   if (i >= n) return;
-  double s = 0.0;
-  for (int c = 0; c < nchunk; ++c) s += (double)partial[(int64_t)c * n + i];
-  if (i < (int64_t)M * E) dWg[i] = (float)s;
-  else if (dbias) dbias[i - (int64_t)M * E] = (float)s;
+  // eight independent running sums keep eight loads in flight; the order of additions is fixed
+  double s[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+  int c = 0;
+  for (; c + 8 <= nchunk; c += 8) {
+#pragma unroll
+    for (int u = 0; u < 8; ++u) s[u] += (double)partial[(int64_t)(c + u) * n + i];
+  }
+  for (; c < nchunk; ++c) s[0] += (double)partial[(int64_t)c * n + i];
+  const double t = ((s[0] + s[1]) + (s[2] + s[3])) + ((s[4] + s[5]) + (s[6] + s[7]));
+  if (i < (int64_t)M * E) dWg[i] = (float)t;
+  else if (dbias) dbias[i - (int64_t)M * E] = (float)t;
 }
 
 }  // namespace
@@ -214,7 +222,7 @@ extern "C" int moe_gate_bwd(const float* dw, const float* w, const int32_t* idx,
   if (bf) hipLaunchKernelGGL(gate_dwg_partial<true>, grid_p, dim3(128), 0, st, x, dlogits, partial, S, M, E, chunk);
   else hipLaunchKernelGGL(gate_dwg_partial<false>, grid_p, dim3(128), 0, st, x, dlogits, partial, S, M, E, chunk);
   const int64_t n = (int64_t)(M + 1) * E;
-  hipLaunchKernelGGL(gate_dwg_reduce, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, partial, nchunk, M, E, dWg,
+  hipLaunchKernelGGL(gate_dwg_reduce, dim3((unsigned)((n + 63) / 64)), dim3(64), 0, st, partial, nchunk, M, E, dWg,
                      dgate_bias);
   return moe::check_launch();
 }
