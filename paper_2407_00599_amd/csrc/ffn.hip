@@ -136,14 +136,14 @@ __device__ __forceinline__ uint4 ldb16(__amdgpu_buffer_rsrc_t r, uint32_t byte_o
 // erf by the rational approximation 7.1.26 of Abramowitz & Stegun (|error| < 1.5e-7), written
 // so that Phi(z) has no cancellation for negative z.  One exp serves GeLU and its derivative.
 __device__ __forceinline__ void gelu_fast(float z, float& g, float& dg) {
-  const float x = fabsf(z) * 0.70710678118654752440f;
-  const float t = __frcp_rn(fmaf(0.3275911f, x, 1.0f));
-  const float ex = __expf(-x * x);  // = exp(-z^2/2)
+  const float x = __builtin_fabsf(z) * 0.70710678118654752440f;
+  const float t = __builtin_amdgcn_rcpf(fmaf(0.3275911f, x, 1.0f));          // v_rcp_f32
+  const float ex = __builtin_amdgcn_exp2f(x * x * -1.4426950408889634f);      // exp(-x^2) = exp(-z^2/2), v_exp_f32
   float poly = fmaf(1.061405429f, t, -1.453152027f);
   poly = fmaf(poly, t, 1.421413741f);
   poly = fmaf(poly, t, -0.284496736f);
   poly = fmaf(poly, t, 0.254829592f);
-  const float tail = 0.5f * poly * t * ex;        // = 1 - Phi(|z|)
+  const float tail = (0.5f * t) * (poly * ex);    // = 1 - Phi(|z|)
   const float cdf = z >= 0.f ? 1.0f - tail : tail;
   g = z * cdf;
   dg = fmaf(z * 0.39894228040143267794f, ex, cdf);

@@ -3,8 +3,9 @@
 //
 // Kernels (wave64 throughout):
 //   gate_logits_small_e : E <= 16.  One wave owns 64/EC tokens; lanes split M, so x is read
-//                         once, coalesced, 16 B per lane.  fp64 accumulation, then a
-//                         halving cross-lane reduction that leaves lane i with output i.
+//                         once, coalesced, 16 B per lane; Wg goes through LDS as fp64, shared
+//                         by the 8 waves of a block.  fp64 accumulation, then a halving
+//                         cross-lane reduction that leaves lane i with output i.
 //   gate_logits_tiled   : any E.  64 tokens x 64 experts per block, LDS-staged K chunks,
 //                         4x4 register tile per thread, fp64 accumulation.
 //   gate_topk           : a group of W = pow2 >= E lanes per token; k rounds of an arg-max
@@ -48,44 +49,73 @@ __device__ __forceinline__ double shfl_xor_f64(double v, int mask) {
   return __hiloint2double(hi, lo);
 }
 
-// EC = experts held per lane (E <= EC), T = 64/EC tokens per wave.
-template <int EC, bool BF16, bool FULL>
-__global__ __launch_bounds__(64) void gate_logits_small_e(const void* __restrict__ x, const float* __restrict__ Wg,
-                                                           const float* __restrict__ bias, float* __restrict__ logits,
-                                                           int64_t S, int M, int E) {
+// EC = experts held per lane (E <= EC), T = 64/EC tokens per wave, 8 waves per block.
+// The block walks M in chunks of 512.  Per chunk it converts Wg[chunk, :] to fp64 once into LDS
+// (shared by the 8 T tokens of the block, laid out [8][64 lanes][EC] so that a lane's EC doubles are
+// contiguous and lanes are adjacent: conflict-free), each lane takes 8 consecutive m of every one of
+// its wave's T tokens (16-byte loads of x, the next chunk requested before this one is multiplied)
+// and runs T*EC fp64 FMAs per m.
+template <int EC, bool BF16>
+__global__ __launch_bounds__(512) void gate_logits_small_e(const void* __restrict__ x, const float* __restrict__ Wg,
+                                                            const float* __restrict__ bias, float* __restrict__ logits,
+                                                            int64_t S, int M, int E) {
   constexpr int T = 64 / EC;
-  const int lane = threadIdx.x & 63;
-  const int64_t wave = (int64_t)blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6);
-  const int64_t t0 = wave * T;
-  if (t0 >= S) return;
+  __shared__ double Ws[8 * 64 * EC];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int64_t t0 = ((int64_t)blockIdx.x * 8 + wave) * T;
   double acc[T * EC];
 #pragma unroll
   for (int i = 0; i < T * EC; ++i) acc[i] = 0.0;
 
-  for (int m0 = lane * 8; m0 < M; m0 += 512) {
-    float xf[T][8];
+  typedef uint4 XRaw[BF16 ? 1 : 2];
+  XRaw xr[T], xn[T];
+  auto load_x = [&](XRaw* dst, int m0) {
 #pragma unroll
-    for (int t = 0; t < T; ++t) load8<BF16>(x, (t0 + t) * (int64_t)M + m0, t0 + t < S, xf[t]);
+    for (int t = 0; t < T; ++t) {
+      const bool ok = (t0 + t < S) && (m0 < M);
+      const int64_t off = (t0 + t) * (int64_t)M + m0;
+      if (BF16) {
+        dst[t][0] = ok ? *reinterpret_cast<const uint4*>(reinterpret_cast<const bf16_t*>(x) + off) : make_uint4(0, 0, 0, 0);
+      } else {
+        const uint4* p = reinterpret_cast<const uint4*>(reinterpret_cast<const float*>(x) + off);
+        dst[t][0] = ok ? p[0] : make_uint4(0, 0, 0, 0);
+        dst[t][BF16 ? 0 : 1] = ok ? p[1] : make_uint4(0, 0, 0, 0);
+      }
+    }
+  };
+  if (BF16) load_x(xr, lane * 8);
+  for (int mb = 0; mb < M; mb += 512) {
+    if (!BF16) load_x(xr, mb + lane * 8);   // fp32 rows are twice as wide: no register room for a prefetch
+    __syncthreads();  // previous chunk's Ws fully consumed
+    for (int i = tid; i < 512 * EC; i += 512) {
+      const int m = i / EC, e = i - m * EC;           // m = lane' * 8 + mm
+      const float wv = (mb + m < M && e < E) ? Wg[(int64_t)(mb + m) * E + e] : 0.f;
+      Ws[(((m & 7) * 64) + (m >> 3)) * EC + e] = (double)wv;
+    }
+    __syncthreads();
+    if (BF16 && mb + 512 < M) load_x(xn, mb + 512 + lane * 8);
 #pragma unroll
     for (int mm = 0; mm < 8; ++mm) {
       double wd[EC];
-      const float* wrow = Wg + (int64_t)(m0 + mm) * E;
-      if (FULL) {  // E == EC: rows of Wg are EC contiguous floats, 16-byte aligned
 #pragma unroll
-        for (int e = 0; e < EC; e += 4) {
-          const float4 q = *reinterpret_cast<const float4*>(wrow + e);
-          wd[e] = (double)q.x; wd[e + 1] = (double)q.y; wd[e + 2] = (double)q.z; wd[e + 3] = (double)q.w;
-        }
-      } else {
-#pragma unroll
-        for (int e = 0; e < EC; ++e) wd[e] = (e < E) ? (double)wrow[e] : 0.0;
-      }
+      for (int e = 0; e < EC; ++e) wd[e] = Ws[(mm * 64 + lane) * EC + e];
 #pragma unroll
       for (int t = 0; t < T; ++t) {
-        const double xd = (double)xf[t][mm];
+        float xf;
+        if (BF16) {
+          const uint32_t word = (&xr[t][0].x)[mm >> 1];
+          xf = __uint_as_float((mm & 1) ? (word & 0xFFFF0000u) : (word << 16));
+        } else {
+          xf = __uint_as_float((&xr[t][mm >> 2].x)[mm & 3]);
+        }
+        const double xd = (double)xf;
 #pragma unroll
         for (int e = 0; e < EC; ++e) acc[t * EC + e] = fma(xd, wd[e], acc[t * EC + e]);
       }
+    }
+    if (BF16 && mb + 512 < M) {
+#pragma unroll
+      for (int t = 0; t < T; ++t) xr[t][0] = xn[t][0];
     }
   }
   // halving reduction over the 64 lanes: after the step with mask h, a lane whose bit h is
@@ -189,7 +219,20 @@ __global__ __launch_bounds__(GATE_TB) void gate_topk(const float* __restrict__ l
   const int r = tid % W;
   const int64_t tb0 = (int64_t)blockIdx.x * GATE_TB;
   constexpr int TPP = GATE_TB / W;  // tokens per pass
+  constexpr int PG = W < 4 ? W : 4;  // passes whose logits are requested together
+  float vv[PG][EPL];
   for (int pass = 0; pass < W; ++pass) {
+    if (pass % PG == 0) {
+#pragma unroll
+      for (int u = 0; u < PG; ++u) {
+        const int64_t tu = tb0 + (pass + u) * TPP + tid / W;
+#pragma unroll
+        for (int i = 0; i < EPL; ++i) {
+          const int e = r + i * W;
+          vv[u][i] = (tu < S && e < E) ? logits[tu * E + e] : 0.f;
+        }
+      }
+    }
     const int64_t t = tb0 + pass * TPP + tid / W;
     const bool live = t < S;
     float v[EPL];
@@ -197,7 +240,11 @@ __global__ __launch_bounds__(GATE_TB) void gate_topk(const float* __restrict__ l
 #pragma unroll
     for (int i = 0; i < EPL; ++i) {
       const int e = r + i * W;
-      v[i] = (live && e < E) ? logits[t * E + e] : 0.f;
+      float val = 0.f;
+#pragma unroll
+      for (int u = 0; u < PG; ++u)
+        if (u == pass % PG) val = vv[u][i];
+      v[i] = val;
       if (!(live && e < E)) taken |= 1u << i;
     }
     float selv[MOE_MAX_K];
@@ -370,19 +417,14 @@ extern "C" int moe_gate_topk(const void* x, int x_dtype, const float* Wg, const 
     const size_t esz = bf ? 2 : 4;
     const void* xs = (const char*)x + (size_t)mp_idx * S * M * esz;
     if (E <= 16) {
-      const int EC = E <= 4 ? 4 : (E <= 8 ? 8 : 16);
+      const int EC = E <= 8 ? 8 : 16;
       const int T = 64 / EC;
-      const int64_t waves = (S + T - 1) / T;
-      const dim3 grid((unsigned)waves), block(64);
-      const bool full = (E == EC);
-#define LAUNCH_SMALL2(ec, b16, fl) \
-  hipLaunchKernelGGL((gate_logits_small_e<ec, b16, fl>), grid, block, 0, st, xs, Wg, gate_bias, logits, S, M, E)
+      const dim3 grid((unsigned)((S + 8 * T - 1) / (8 * T))), block(512);
 #define LAUNCH_SMALL(ec) do { \
-    if (bf) { if (full) LAUNCH_SMALL2(ec, true, true); else LAUNCH_SMALL2(ec, true, false); } \
-    else { if (full) LAUNCH_SMALL2(ec, false, true); else LAUNCH_SMALL2(ec, false, false); } } while (0)
-      if (EC == 4) LAUNCH_SMALL(4); else if (EC == 8) LAUNCH_SMALL(8); else LAUNCH_SMALL(16);
+    if (bf) hipLaunchKernelGGL((gate_logits_small_e<ec, true>), grid, block, 0, st, xs, Wg, gate_bias, logits, S, M, E); \
+    else hipLaunchKernelGGL((gate_logits_small_e<ec, false>), grid, block, 0, st, xs, Wg, gate_bias, logits, S, M, E); } while (0)
+      if (EC == 8) LAUNCH_SMALL(8); else LAUNCH_SMALL(16);
 #undef LAUNCH_SMALL
-#undef LAUNCH_SMALL2
     } else {
       const dim3 grid((unsigned)((S + 63) / 64), (unsigned)((E + 63) / 64)), block(256);
       if (bf) hipLaunchKernelGGL((gate_logits_tiled<true>), grid, block, 0, st, xs, Wg, gate_bias, logits, S, M, E);

@@ -18,8 +18,8 @@ using namespace moe;
 
 constexpr int DX_TOK = 8;        // tokens per thread step in gate_dx
 constexpr int DX_TOK_BLK = 8;    // tokens per block in gate_dx
-// tokens per partial sum in gate_dwg_partial: at least 32, and at most 256 partial sums
-inline int dwg_chunk(int64_t S) { const int64_t c = (S + 255) / 256; return (int)(c < 32 ? 32 : c); }
+// tokens per partial sum in gate_dwg_partial: a multiple of 8, at least 8, and at most 256 partial sums
+inline int dwg_chunk(int64_t S) { const int64_t c = (S + 255) / 256; return (int)(c < 8 ? 8 : (c + 7) / 8 * 8); }
 
 __global__ __launch_bounds__(256) void gate_dlogits(const float* __restrict__ dw, const float* __restrict__ w,
                                                     const int32_t* __restrict__ idx, const float* __restrict__ logits,
@@ -75,7 +75,9 @@ __device__ __forceinline__ void st8g(void* base, int64_t off, const float* f) {
 }
 
 // grid: (ceil(M/8/128), ceil(S/DX_TOK_BLK)); block 128 threads, thread -> 8 consecutive m.
-template <bool BF16>
+// EC experts of Wg are held in registers at a time (EC = 8 when E <= 8, else 16); the old dx rows of
+// a step are requested before the FMAs so that their latency is covered.
+template <bool BF16, int EC>
 __global__ __launch_bounds__(128) void gate_dx(const float* __restrict__ dl, const float* __restrict__ Wg,
                                                void* __restrict__ dx, int64_t S, int M, int E, int accumulate) {
   const int m0 = (blockIdx.x * 128 + threadIdx.x) * 8;
@@ -84,21 +86,26 @@ __global__ __launch_bounds__(128) void gate_dx(const float* __restrict__ dl, con
   for (int64_t t0 = tb; t0 < tb + DX_TOK_BLK && t0 < S; t0 += DX_TOK) {
     float acc[DX_TOK][8];
 #pragma unroll
-    for (int i = 0; i < DX_TOK; ++i)
+    for (int i = 0; i < DX_TOK; ++i) {
+      if (accumulate && t0 + i < S) {
+        ld8g<BF16>(dx, (t0 + i) * (int64_t)M + m0, acc[i]);
+      } else {
 #pragma unroll
-      for (int q = 0; q < 8; ++q) acc[i][q] = 0.f;
-    for (int e0 = 0; e0 < E; e0 += 16) {
-      float wr[8][16];
+        for (int q = 0; q < 8; ++q) acc[i][q] = 0.f;
+      }
+    }
+    for (int e0 = 0; e0 < E; e0 += EC) {
+      float wr[8][EC];
 #pragma unroll
       for (int q = 0; q < 8; ++q)
 #pragma unroll
-        for (int e = 0; e < 16; ++e) wr[q][e] = (e0 + e < E) ? Wg[(int64_t)(m0 + q) * E + e0 + e] : 0.f;
+        for (int e = 0; e < EC; ++e) wr[q][e] = (e0 + e < E) ? Wg[(int64_t)(m0 + q) * E + e0 + e] : 0.f;
 #pragma unroll
       for (int i = 0; i < DX_TOK; ++i) {
         const int64_t t = t0 + i;
         if (t < S) {
 #pragma unroll
-          for (int e = 0; e < 16; ++e) {
+          for (int e = 0; e < EC; ++e) {
             const float d = (e0 + e < E) ? dl[t * E + e0 + e] : 0.f;
 #pragma unroll
             for (int q = 0; q < 8; ++q) acc[i][q] = fmaf(d, wr[q][e], acc[i][q]);
@@ -107,23 +114,13 @@ __global__ __launch_bounds__(128) void gate_dx(const float* __restrict__ dl, con
       }
     }
 #pragma unroll
-    for (int i = 0; i < DX_TOK; ++i) {
-      const int64_t t = t0 + i;
-      if (t < S) {
-        if (accumulate) {
-          float old[8];
-          ld8g<BF16>(dx, t * (int64_t)M + m0, old);
-#pragma unroll
-          for (int q = 0; q < 8; ++q) acc[i][q] += old[q];
-        }
-        st8g<BF16>(dx, t * (int64_t)M + m0, acc[i]);
-      }
-    }
+    for (int i = 0; i < DX_TOK; ++i)
+      if (t0 + i < S) st8g<BF16>(dx, (t0 + i) * (int64_t)M + m0, acc[i]);
   }
 }
 
 // grid: (ceil(M/8/128), nchunk); partial[chunk][m][e] for m < M, plus row m = M for dbias.
-template <bool BF16>
+template <bool BF16, int EC>
 __global__ __launch_bounds__(128) void gate_dwg_partial(const void* __restrict__ x, const float* __restrict__ dl,
                                                         float* __restrict__ partial, int64_t S, int M, int E,
                                                         int chunk) {
@@ -132,18 +129,31 @@ __global__ __launch_bounds__(128) void gate_dwg_partial(const void* __restrict__
   const int64_t te = (tb + chunk < S) ? tb + chunk : S;
   float* out = partial + (int64_t)blockIdx.y * (M + 1) * E;
   if (m0 < M) {
-    for (int e0 = 0; e0 < E; e0 += 16) {
-      float acc[8][16];
+    for (int e0 = 0; e0 < E; e0 += EC) {
+      float acc[8][EC];
 #pragma unroll
       for (int q = 0; q < 8; ++q)
 #pragma unroll
-        for (int e = 0; e < 16; ++e) acc[q][e] = 0.f;
-#pragma unroll 4
-      for (int64_t t = tb; t < te; ++t) {
+        for (int e = 0; e < EC; ++e) acc[q][e] = 0.f;
+      int64_t t = tb;
+      for (; t + 4 <= te; t += 4) {       // four rows of x in flight
+        float xf[4][8];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) ld8g<BF16>(x, (t + u) * (int64_t)M + m0, xf[u]);
+#pragma unroll
+        for (int u = 0; u < 4; ++u)
+#pragma unroll
+          for (int e = 0; e < EC; ++e) {
+            const float d = (e0 + e < E) ? dl[(t + u) * E + e0 + e] : 0.f;
+#pragma unroll
+            for (int q = 0; q < 8; ++q) acc[q][e] = fmaf(xf[u][q], d, acc[q][e]);
+          }
+      }
+      for (; t < te; ++t) {
         float xf[8];
         ld8g<BF16>(x, t * (int64_t)M + m0, xf);
 #pragma unroll
-        for (int e = 0; e < 16; ++e) {
+        for (int e = 0; e < EC; ++e) {
           const float d = (e0 + e < E) ? dl[t * E + e0 + e] : 0.f;
 #pragma unroll
           for (int q = 0; q < 8; ++q) acc[q][e] = fmaf(xf[q], d, acc[q][e]);
@@ -152,7 +162,7 @@ __global__ __launch_bounds__(128) void gate_dwg_partial(const void* __restrict__
 #pragma unroll
       for (int q = 0; q < 8; ++q)
 #pragma unroll
-        for (int e = 0; e < 16; ++e)
+        for (int e = 0; e < EC; ++e)
           if (e0 + e < E) out[(int64_t)(m0 + q) * E + e0 + e] = acc[q][e];
     }
   }
@@ -163,6 +173,142 @@ __global__ __launch_bounds__(128) void gate_dwg_partial(const void* __restrict__
       out[(int64_t)M * E + e] = s;
     }
   }
+}
+
+// ---- fast paths for E <= 16 (EC = 8 or 16 holds all experts): dl rows and the Wg tile go through
+// LDS with coalesced global accesses, zero-padded to EC, so the FMA loops have no conditions ----
+constexpr int GB_TOK = 32;                 // tokens per block
+constexpr int GB_MT = 1024;                // m per block (128 threads x 8)
+constexpr int GB_PITCH = GB_MT + 8;        // row pitch of the transposed Wg tile [e][m] in LDS (floats)
+
+// dx[t, m] (+)= sum_e dl[t,e] Wg[m,e]
+template <bool BF16, int EC>
+__global__ __launch_bounds__(128) void gate_dx_fast(const float* __restrict__ dl, const float* __restrict__ Wg,
+                                                    void* __restrict__ dx, int64_t S, int M, int E, int accumulate,
+                                                    int tok_blk /* <= GB_TOK, multiple of 8 */) {
+  constexpr int TS = EC <= 8 ? 8 : 4;   // tokens per step (register budget)
+  __shared__ __attribute__((aligned(16))) float wgs[EC * GB_PITCH];
+  __shared__ __attribute__((aligned(16))) float dls[GB_TOK * EC];
+  const int tid = threadIdx.x;
+  const int mb = blockIdx.x * GB_MT;
+  const int64_t tb = (int64_t)blockIdx.y * tok_blk;
+  for (int i = tid; i < GB_MT * EC; i += 128) {
+    const int m = i / EC, e = i - m * EC;
+    wgs[e * GB_PITCH + m] = (mb + m < M && e < E) ? Wg[(int64_t)(mb + m) * E + e] : 0.f;
+  }
+  for (int i = tid; i < tok_blk * EC; i += 128) {
+    const int t = i / EC, e = i - t * EC;
+    dls[i] = (tb + t < S && e < E) ? dl[(tb + t) * E + e] : 0.f;
+  }
+  __syncthreads();
+  const int ml = tid * 8, m0 = mb + ml;
+  if (m0 >= M) return;
+  float wr[EC][8];
+#pragma unroll
+  for (int e = 0; e < EC; ++e) {
+    const float4 a = *reinterpret_cast<const float4*>(&wgs[e * GB_PITCH + ml]);
+    const float4 b = *reinterpret_cast<const float4*>(&wgs[e * GB_PITCH + ml + 4]);
+    wr[e][0] = a.x; wr[e][1] = a.y; wr[e][2] = a.z; wr[e][3] = a.w;
+    wr[e][4] = b.x; wr[e][5] = b.y; wr[e][6] = b.z; wr[e][7] = b.w;
+  }
+#pragma unroll 1
+  for (int t0 = 0; t0 < tok_blk; t0 += TS) {
+    float acc[TS][8];
+#pragma unroll
+    for (int i = 0; i < TS; ++i) {
+      if (accumulate && tb + t0 + i < S) {
+        ld8g<BF16>(dx, (tb + t0 + i) * (int64_t)M + m0, acc[i]);
+      } else {
+#pragma unroll
+        for (int q = 0; q < 8; ++q) acc[i][q] = 0.f;
+      }
+    }
+#pragma unroll
+    for (int i = 0; i < TS; ++i) {
+#pragma unroll
+      for (int e4 = 0; e4 < EC; e4 += 4) {
+        const float4 d = *reinterpret_cast<const float4*>(&dls[(t0 + i) * EC + e4]);   // same address in all lanes
+        const float dv[4] = {d.x, d.y, d.z, d.w};
+#pragma unroll
+        for (int u = 0; u < 4; ++u)
+#pragma unroll
+          for (int q = 0; q < 8; ++q) acc[i][q] = fmaf(dv[u], wr[e4 + u][q], acc[i][q]);
+      }
+    }
+#pragma unroll
+    for (int i = 0; i < TS; ++i)
+      if (tb + t0 + i < S) st8g<BF16>(dx, (tb + t0 + i) * (int64_t)M + m0, acc[i]);
+  }
+}
+
+// partial[chunk][m][e] = sum over the chunk's tokens of x[t,m] dl[t,e]; the results leave through LDS
+// so that the [m][e] rows are written contiguously
+template <bool BF16, int EC>
+__global__ __launch_bounds__(128) void gate_dwg_partial_fast(const void* __restrict__ x, const float* __restrict__ dl,
+                                                             float* __restrict__ partial, int64_t S, int M, int E,
+                                                             int chunk) {
+  __shared__ __attribute__((aligned(16))) float outs[EC * GB_PITCH];
+  __shared__ __attribute__((aligned(16))) float dls[GB_TOK * EC];
+  const int tid = threadIdx.x;
+  const int mb = blockIdx.x * GB_MT;
+  const int ml = tid * 8, m0 = mb + ml;
+  const int64_t tb = (int64_t)blockIdx.y * chunk;
+  const int64_t te = (tb + chunk < S) ? tb + chunk : S;
+  float* out = partial + (int64_t)blockIdx.y * (M + 1) * E;
+  float acc[EC][8];
+#pragma unroll
+  for (int e = 0; e < EC; ++e)
+#pragma unroll
+    for (int q = 0; q < 8; ++q) acc[e][q] = 0.f;
+  float colsum = 0.f;   // thread e < E of block column 0 also sums dl[:, e] for the bias row
+  for (int64_t t0 = tb; t0 < te; t0 += GB_TOK) {
+    __syncthreads();
+    for (int i = tid; i < GB_TOK * EC; i += 128) {
+      const int t = i / EC, e = i - t * EC;
+      dls[i] = (t0 + t < te && e < E) ? dl[(t0 + t) * E + e] : 0.f;
+    }
+    __syncthreads();
+    if (blockIdx.x == 0 && tid < EC)
+      for (int t = 0; t < GB_TOK; ++t) colsum += dls[t * EC + tid];
+    if (m0 < M) {
+      const int nt = (int)((te - t0 < GB_TOK) ? te - t0 : GB_TOK);
+#pragma unroll 1
+      for (int ts = 0; ts < nt; ts += 4) {
+        float xf[4][8];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+          if (t0 + ts + u < te) {
+            ld8g<BF16>(x, (t0 + ts + u) * (int64_t)M + m0, xf[u]);
+          } else {
+#pragma unroll
+            for (int q = 0; q < 8; ++q) xf[u][q] = 0.f;
+          }
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u)
+#pragma unroll
+          for (int e4 = 0; e4 < EC; e4 += 4) {
+            const float4 d = *reinterpret_cast<const float4*>(&dls[(ts + u) * EC + e4]);
+            const float dv[4] = {d.x, d.y, d.z, d.w};
+#pragma unroll
+            for (int v = 0; v < 4; ++v)
+#pragma unroll
+              for (int q = 0; q < 8; ++q) acc[e4 + v][q] = fmaf(xf[u][q], dv[v], acc[e4 + v][q]);
+          }
+      }
+    }
+  }
+#pragma unroll
+  for (int e = 0; e < EC; ++e) {
+    *reinterpret_cast<float4*>(&outs[e * GB_PITCH + ml]) = make_float4(acc[e][0], acc[e][1], acc[e][2], acc[e][3]);
+    *reinterpret_cast<float4*>(&outs[e * GB_PITCH + ml + 4]) = make_float4(acc[e][4], acc[e][5], acc[e][6], acc[e][7]);
+  }
+  __syncthreads();
+  for (int i = tid; i < GB_MT * EC; i += 128) {
+    const int m = i / EC, e = i - m * EC;
+    if (mb + m < M && e < E) out[(int64_t)(mb + m) * E + e] = outs[e * GB_PITCH + m];
+  }
+  if (blockIdx.x == 0 && tid < E && tid < EC) out[(int64_t)M * E + tid] = colsum;
 }
 
 __global__ __launch_bounds__(64) void gate_dwg_reduce(const float* __restrict__ partial, int nchunk, int M, int E,
@@ -213,14 +359,27 @@ extern "C" int moe_gate_bwd(const float* dw, const float* w, const int32_t* idx,
                      norm, dlogits);
   const unsigned gm = (unsigned)((M / 8 + 127) / 128);
   const dim3 grid_dx(gm, (unsigned)((S + DX_TOK_BLK - 1) / DX_TOK_BLK));
-  if (bf) hipLaunchKernelGGL(gate_dx<true>, grid_dx, dim3(128), 0, st, dlogits, Wg, dx, S, M, E, dx_accumulate);
-  else hipLaunchKernelGGL(gate_dx<false>, grid_dx, dim3(128), 0, st, dlogits, Wg, dx, S, M, E, dx_accumulate);
+#define MOE_GATE_BWD_LAUNCH(kern, grid, ...)                                                        \
+  do {                                                                                              \
+    if (bf) { if (E <= 8) hipLaunchKernelGGL((kern<true, 8>), grid, dim3(128), 0, st, __VA_ARGS__); \
+              else hipLaunchKernelGGL((kern<true, 16>), grid, dim3(128), 0, st, __VA_ARGS__); }     \
+    else { if (E <= 8) hipLaunchKernelGGL((kern<false, 8>), grid, dim3(128), 0, st, __VA_ARGS__);   \
+           else hipLaunchKernelGGL((kern<false, 16>), grid, dim3(128), 0, st, __VA_ARGS__); }       \
+  } while (0)
+  const int mblocks = (M + GB_MT - 1) / GB_MT;
+  const int tok_blk = ((int64_t)mblocks * ((S + GB_TOK - 1) / GB_TOK) >= 2048) ? GB_TOK : 8;   // keep the grid wide
+  const dim3 grid_fx((unsigned)mblocks, (unsigned)((S + tok_blk - 1) / tok_blk));
+  // the LDS-staged kernel pays off once there is enough work per staged Wg tile
+  if (E <= 16 && tok_blk == GB_TOK) MOE_GATE_BWD_LAUNCH(gate_dx_fast, grid_fx, dlogits, Wg, dx, S, M, E, dx_accumulate, tok_blk);
+  else MOE_GATE_BWD_LAUNCH(gate_dx, grid_dx, dlogits, Wg, dx, S, M, E, dx_accumulate);
   const int chunk = dwg_chunk(S);
   const int nchunk = (int)((S + chunk - 1) / chunk);
   const dim3 grid_p(gm, (unsigned)nchunk);
   float* partial = (float*)ws;
-  if (bf) hipLaunchKernelGGL(gate_dwg_partial<true>, grid_p, dim3(128), 0, st, x, dlogits, partial, S, M, E, chunk);
-  else hipLaunchKernelGGL(gate_dwg_partial<false>, grid_p, dim3(128), 0, st, x, dlogits, partial, S, M, E, chunk);
+  const dim3 grid_fp((unsigned)((M + GB_MT - 1) / GB_MT), (unsigned)nchunk);
+  if (E <= 16) MOE_GATE_BWD_LAUNCH(gate_dwg_partial_fast, grid_fp, x, dlogits, partial, S, M, E, chunk);
+  else MOE_GATE_BWD_LAUNCH(gate_dwg_partial, grid_p, x, dlogits, partial, S, M, E, chunk);
+#undef MOE_GATE_BWD_LAUNCH
   const int64_t n = (int64_t)(M + 1) * E;
   hipLaunchKernelGGL(gate_dwg_reduce, dim3((unsigned)((n + 63) / 64)), dim3(64), 0, st, partial, nchunk, M, E, dWg,
                      dgate_bias);

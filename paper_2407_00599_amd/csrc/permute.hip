@@ -93,24 +93,38 @@ __global__ __launch_bounds__(256) void combine_rows(const void* __restrict__ Yre
       }
     }
   }
-  for (int m = lane * 8; m < M; m += 512) {
-    float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+  // two 512-element chunks per step: twice as many independent loads in flight per lane
+  for (int m = lane * 8; m < M; m += 1024) {
+    const bool two = m + 512 < M;
+    float acc0[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+    float acc1[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
 #pragma unroll
     for (int j = 0; j < MOE_MAX_K; ++j) {
       if (j < k && src[j] >= 0) {
-        float r[8];
-        ld8<BF16>(Yret, src[j] + m, r);
+        float r0[8], r1[8];
+        ld8<BF16>(Yret, src[j] + m, r0);
+        if (two) ld8<BF16>(Yret, src[j] + m + 512, r1);
         for (int p = 1; p < n_part; ++p) {
-          float q[8];
-          ld8<BF16>(Yret, src[j] + m + p * part_stride, q);
+          float q0[8], q1[8];
+          ld8<BF16>(Yret, src[j] + m + p * part_stride, q0);
+          if (two) ld8<BF16>(Yret, src[j] + m + 512 + p * part_stride, q1);
 #pragma unroll
-          for (int i = 0; i < 8; ++i) r[i] += q[i];
+          for (int i = 0; i < 8; ++i) r0[i] += q0[i];
+          if (two) {
+#pragma unroll
+            for (int i = 0; i < 8; ++i) r1[i] += q1[i];
+          }
         }
 #pragma unroll
-        for (int i = 0; i < 8; ++i) acc[i] = fmaf(wt[j], r[i], acc[i]);
+        for (int i = 0; i < 8; ++i) acc0[i] = fmaf(wt[j], r0[i], acc0[i]);
+        if (two) {
+#pragma unroll
+          for (int i = 0; i < 8; ++i) acc1[i] = fmaf(wt[j], r1[i], acc1[i]);
+        }
       }
     }
-    st8<BF16>(y, t * (int64_t)M + m, acc);
+    st8<BF16>(y, t * (int64_t)M + m, acc0);
+    if (two) st8<BF16>(y, t * (int64_t)M + m + 512, acc1);
   }
 }
 
@@ -123,28 +137,44 @@ __global__ __launch_bounds__(256) void combine_dw(const void* __restrict__ dy, c
   const int lane = threadIdx.x & 63;
   const int64_t t = (int64_t)blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6);
   if (t >= S) return;
-  for (int j = 0; j < k; ++j) {
-    const int c = slot[t * k + j];
-    float dot = 0.f;
-    if (c >= 0) {
-      const int64_t src = ((int64_t)idx[t * k + j] * C + c) * M;
-      for (int m = lane * 8; m < M; m += 512) {
-        float g[8], r[8];
-        ld8<BF16>(dy, t * (int64_t)M + m, g);
-        ld8<BF16>(Yret, src + m, r);
+  int64_t src[MOE_MAX_K];
+  float dot[MOE_MAX_K];
+#pragma unroll
+  for (int j = 0; j < MOE_MAX_K; ++j) {
+    src[j] = -1; dot[j] = 0.f;
+    if (j < k) {
+      const int c = slot[t * k + j];
+      if (c >= 0) src[j] = ((int64_t)idx[t * k + j] * C + c) * M;
+    }
+  }
+  // dy is read once per chunk and dotted with the rows of all surviving choices
+  for (int m = lane * 8; m < M; m += 512) {
+    float g[8];
+    ld8<BF16>(dy, t * (int64_t)M + m, g);
+#pragma unroll
+    for (int j = 0; j < MOE_MAX_K; ++j) {
+      if (j < k && src[j] >= 0) {
+        float r[8];
+        ld8<BF16>(Yret, src[j] + m, r);
         for (int p = 1; p < n_part; ++p) {
           float q[8];
-          ld8<BF16>(Yret, src + m + p * part_stride, q);
+          ld8<BF16>(Yret, src[j] + m + p * part_stride, q);
 #pragma unroll
           for (int i = 0; i < 8; ++i) r[i] += q[i];
         }
 #pragma unroll
-        for (int i = 0; i < 8; ++i) dot = fmaf(g[i], r[i], dot);
+        for (int i = 0; i < 8; ++i) dot[j] = fmaf(g[i], r[i], dot[j]);
       }
-#pragma unroll
-      for (int o = 32; o >= 1; o >>= 1) dot += __shfl_xor(dot, o, 64);
     }
-    if (lane == 0) dw[t * k + j] = dot;
+  }
+#pragma unroll
+  for (int j = 0; j < MOE_MAX_K; ++j) {
+    if (j < k) {
+      float d = dot[j];
+#pragma unroll
+      for (int o = 32; o >= 1; o >>= 1) d += __shfl_xor(d, o, 64);
+      if (lane == 0) dw[t * k + j] = d;
+    }
   }
 }
 
