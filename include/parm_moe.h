@@ -129,8 +129,9 @@ size_t moe_ffn_workspace_bytes(int dtype, int n_src, int G, int64_t C, int M, in
 
 /* Tuning knob for the bf16 grouped GEMMs.  0 = choose per GEMM from its tile count (default);
  * 1 = 128x128 tiles, register-staged; 2 = 256x256 LDS-DMA kernel with 4 waves; 6 = the same
- * with 8 waves (the default for all but tiny problems); 3, 4, 5 = 256x256 register-staged
- * variants kept for comparison.  Process-wide; affects speed only, never results beyond fp32
+ * with 8 waves (the default for all but tiny problems); 7 = the 8-wave kernel with 192-row tiles
+ * wherever the operand layout allows (auto picks it when it fills the chip better);
+ * 3, 4, 5 = 256x256 register-staged variants kept for comparison.  Process-wide; affects speed only, never results beyond fp32
  * summation order.  Returns MOE_EINVAL for other values. */
 int moe_ffn_set_tile(int tile);
 

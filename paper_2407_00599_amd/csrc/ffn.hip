@@ -508,8 +508,8 @@ __global__ __launch_bounds__(WM * WN * 64) void ffn_gemm_bf16(const GemmArgs p) 
 // memory: per 32-row block it writes bf16 results in [32][CW] row-major form (CW = columns of the
 // wave tile, row pitch 2 CW + 16 bytes), reads them back row-wise and stores them; the GeLU
 // epilogues stage their second output, and the saved pre-activation they read, the same way.
-template <int KIND, int EPI, int NBK>
-__device__ __forceinline__ void store_tile_lds(const GemmArgs& p, f32x16_t (&acc)[4][NBK], char* wave_lds, int g,
+template <int KIND, int EPI, int MB, int NBK>
+__device__ __forceinline__ void store_tile_lds(const GemmArgs& p, f32x16_t (&acc)[MB][NBK], char* wave_lds, int g,
                                                int mbase, int nbase, int lane) {
   constexpr int CW = 32 * NBK;            // columns of the wave tile
   constexpr int PITCH_B = 2 * CW + 16;    // staged row pitch, bytes
@@ -529,7 +529,7 @@ __device__ __forceinline__ void store_tile_lds(const GemmArgs& p, f32x16_t (&acc
   // accumulator phase: row lane % 32, for block j and q4: 4 columns at 32 j + 8 q4 + 4 (lane / 32)
   const int acc_off = (lane & 31) * PITCH_B + (lane >> 5) * 8;
 #pragma unroll
-  for (int i = 0; i < 4; ++i) {
+  for (int i = 0; i < MB; ++i) {
     int64_t crow[NT_];  // global row offsets of the rows this lane touches in the row-wise phase
     bool row_ok[NT_];
 #pragma unroll
@@ -648,12 +648,15 @@ __device__ __forceinline__ void lds_read_nc(Frag& f, uint32_t addr_lo, uint32_t 
 }
 __device__ __forceinline__ void ready(Frag& f) { asm volatile("" : "+v"(f.q)); }
 
-// WN = waves along n: 2 (4 waves, 128x128 per wave) or 4 (8 waves, 128x64 per wave, two per SIMD)
-template <int KIND, int EPI, int WN>
+// WN = waves along n: 2 (4 waves, 128x128 per wave) or 4 (8 waves, 128x64 per wave, two per SIMD).
+// TMR = rows of the output tile: 256, or 192 (three 32-row blocks per wave; only for operands A
+// with k contiguous) for problems whose 256-row tiling would leave many compute units idle.
+template <int KIND, int EPI, int WN, int TMR = 256>
 __global__ __launch_bounds__(128 * WN) void ffn_gemm_dma(const GemmArgs p) {
   constexpr bool A_NC = (KIND == KIND_TN);                     // A has k as the slow index
   constexpr bool B_NC = (KIND == KIND_NN || KIND == KIND_TN);  // B has k as the slow index
-  constexpr int MB = 4, NBK = 8 / WN;     // 32x32 blocks per wave tile
+  static_assert(TMR == 256 || (TMR == 192 && !A_NC && WN == 4), "unsupported tile height");
+  constexpr int MB = TMR / 64, NBK = 8 / WN;     // 32x32 blocks per wave tile
   constexpr int RPW = 8 / WN;             // requests per wave per operand per k tile (16 in all)
 
   __shared__ __attribute__((aligned(1024))) char smem[DSTAGES * DSTAGE];
@@ -664,7 +667,7 @@ __global__ __launch_bounds__(128 * WN) void ffn_gemm_dma(const GemmArgs p) {
 
   int g, tm, tn;
   if (!map_tile(p, g, tm, tn)) return;
-  const int m0 = tm * DT, n0 = tn * DT;
+  const int m0 = tm * TMR, n0 = tn * DT;
 
   const int64_t b_base = (int64_t)g * p.b_goff + p.b_off;
   const __amdgpu_buffer_rsrc_t rA = make_rsrc(p.A, (uint32_t)p.a_bytes);
@@ -686,9 +689,10 @@ __global__ __launch_bounds__(128 * WN) void ffn_gemm_dma(const GemmArgs p) {
   for (int j = 0; j < RPW; ++j) {
     const int q = wave * RPW + j;
     if (!A_NC) {
-      const int r = m0 + q * 16 + (lane >> 2);
+      const int rt = q * 16 + (lane >> 2);   // rows past a 192-row tile are never fetched
+      const int r = m0 + rt;
       a_k[j] = kc_c * 8;
-      a_req[j] = (r < p.Mdim) ? (uint32_t)((phys_row(r, g, p.G, p.Cc) * p.lda + kc_c * 8) * 2) : OOB;
+      a_req[j] = (rt < TMR && r < p.Mdim) ? (uint32_t)((phys_row(r, g, p.G, p.Cc) * p.lda + kc_c * 8) * 2) : OOB;
     } else {
       const int k = 2 * q + (lane >> 5);
       const int col = m0 + (((lane & 31) ^ (4 * (k & 3))) * 8);
@@ -747,7 +751,7 @@ __global__ __launch_bounds__(128 * WN) void ffn_gemm_dma(const GemmArgs p) {
   {
     const int b = lane >> 4, s = lane & 15;
     if (!A_NC) {
-      const int row = wm * 128 + (lane & 31);
+      const int row = wm * (32 * MB) + (lane & 31);
       for (int kk = 0; kk < 2; ++kk)
         a_fr[kk][0] = a_fr[kk][1] = a_fr[kk][2] = a_fr[kk][3] =
             row * 64 + (((2 * kk + (lane >> 5)) ^ ((lane >> 2) & 3)) * 16);
@@ -803,10 +807,11 @@ __global__ __launch_bounds__(128 * WN) void ffn_gemm_dma(const GemmArgs p) {
       }
     } else {
       if (!A_NC) {
-        lds_read_kc<2 * 2048>(fa[kk][2], st + a_fr[kk][0]); lds_read_kc<3 * 2048>(fa[kk][3], st + a_fr[kk][0]);
+        lds_read_kc<2 * 2048>(fa[kk][2], st + a_fr[kk][0]);
+        if (MB == 4) lds_read_kc<3 * 2048>(fa[kk][MB - 1], st + a_fr[kk][0]);
       } else {
         lds_read_nc<kk * 8192>(fa[kk][2], st + a_fr[0][2], st + a_fr[1][2]);
-        lds_read_nc<kk * 8192>(fa[kk][3], st + a_fr[0][3], st + a_fr[1][3]);
+        lds_read_nc<kk * 8192>(fa[kk][MB - 1], st + a_fr[0][3], st + a_fr[1][3]);
       }
     }
   };
@@ -867,6 +872,7 @@ __global__ __launch_bounds__(128 * WN) void ffn_gemm_dma(const GemmArgs p) {
 #pragma unroll
     for (int i = 1; i < MB; ++i) {
       load_frags(kt + 1, K0{}, i - 1);
+      if (MB == 3 && i == 2) load_frags(kt + 1, K0{}, 2);
       if (i - 1 < RPW) request1(kt + 3, 0, i - 1);
       __builtin_amdgcn_sched_barrier(0);
       mfma_row(1, i);
@@ -877,7 +883,7 @@ __global__ __launch_bounds__(128 * WN) void ffn_gemm_dma(const GemmArgs p) {
   __builtin_amdgcn_s_waitcnt(0x0070);  // drain trailing (empty) requests and fragment reads before LDS is released
 
   __syncthreads();  // every wave is done reading fragments: the stage memory can be reused
-  store_tile_lds<KIND, EPI, NBK>(p, acc, smem + wave * (DSTAGES * DSTAGE / (2 * WN)), g, m0 + wm * 128,
+  store_tile_lds<KIND, EPI, MB, NBK>(p, acc, smem + wave * (DSTAGES * DSTAGE / (2 * WN)), g, m0 + wm * (32 * MB),
                                  n0 + wn * (32 * NBK), lane);
 }
 
@@ -981,6 +987,17 @@ __global__ __launch_bounds__(256) void ffn_gemm_f32(const GemmArgs p) {
 // ------------------------------------------------------------------------------------------
 int g_tile_pref = 0;  // 0 auto, 1 = 128x128, 2 = 256x256
 
+int num_cus() {
+  static int n = 0;   // same on every device of a node
+  if (n == 0) {
+    int dev = 0, v = 0;
+    if (hipGetDevice(&dev) == hipSuccess &&
+        hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && v > 0) n = v;
+    else n = 256;
+  }
+  return n;
+}
+
 template <int KIND, int EPI>
 void launch_gemm(GemmArgs a, int dtype, hipStream_t st) {
   if (dtype == MOE_F32) {
@@ -999,11 +1016,22 @@ void launch_gemm(GemmArgs a, int dtype, hipStream_t st) {
   if (g_tile_pref == 1) big = false;
   if (g_tile_pref >= 2) big = true;
   const int T = big ? 256 : 128;
-  a.tiles_m = (a.Mdim + T - 1) / T;
   a.tiles_n = (a.Ndim + T - 1) / T;
+  // 192-row tiles when they need fewer rounds of the chip's compute units (weighted by tile height)
+  bool low = false;
+  if (big && KIND != KIND_TN && (g_tile_pref == 0 || g_tile_pref == 7)) {
+    const int64_t t256 = (int64_t)a.G * ((a.Mdim + 255) / 256) * a.tiles_n;
+    const int64_t t192 = (int64_t)a.G * ((a.Mdim + 191) / 192) * a.tiles_n;
+    const int64_t cu = num_cus();
+    low = g_tile_pref == 7 || ((t192 + cu - 1) / cu) * 192 < ((t256 + cu - 1) / cu) * 256;
+  }
+  const int TMh = low ? 192 : T;
+  a.tiles_m = (a.Mdim + TMh - 1) / TMh;
   a.total_tiles = a.G * a.tiles_m * a.tiles_n;
   const dim3 grid((unsigned)(((a.total_tiles + 7) / 8) * 8));
-  if (big && (g_tile_pref == 0 || g_tile_pref == 6))
+  if (low) {
+    if constexpr (KIND != KIND_TN) hipLaunchKernelGGL((ffn_gemm_dma<KIND, EPI, 4, 192>), grid, dim3(512), 0, st, a);
+  } else if (big && (g_tile_pref == 0 || g_tile_pref == 6 || g_tile_pref == 7))
     hipLaunchKernelGGL((ffn_gemm_dma<KIND, EPI, 4>), grid, dim3(512), 0, st, a);
   else if (big && g_tile_pref == 2)
     hipLaunchKernelGGL((ffn_gemm_dma<KIND, EPI, 2>), grid, dim3(256), 0, st, a);
@@ -1031,7 +1059,7 @@ int check_ffn_shape(int dtype, int n_src, int G, int64_t C, int M, int H, int es
 }  // namespace
 
 extern "C" int moe_ffn_set_tile(int tile) {
-  if (tile < 0 || tile > 6) return MOE_EINVAL;
+  if (tile < 0 || tile > 7) return MOE_EINVAL;
   g_tile_pref = tile;
   return MOE_OK;
 }

@@ -123,7 +123,7 @@ def test_ffn_argument_checks(L):
     assert fwd(ws=None) == -5
     assert L.moe_expert_ffn_bwd(A, A, A, A, A, 1, 1, 2, 10, 64, 128, 0, 1, A, A, None, A, 1 << 30, None) == -6
     assert L.moe_expert_ffn_bwd(A, A, A, A, A, 1, 1, 2, 10, 64, 128, 0, 1, A, A, A, A, 64, None) == -5
-    assert L.moe_ffn_set_tile(7) == -1 and L.moe_ffn_set_tile(-1) == -1 and L.moe_ffn_set_tile(0) == 0
+    assert L.moe_ffn_set_tile(8) == -1 and L.moe_ffn_set_tile(-1) == -1 and L.moe_ffn_set_tile(0) == 0
 
 
 def test_gate_bwd_argument_checks(L):

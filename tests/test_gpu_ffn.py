@@ -39,6 +39,9 @@ CASES = [
     (1, 2, 300, 512, 768, 1, 0, "bf16", 6),
     (2, 3, 200, 264, 1040, 2, 0, "bf16", 6),
     (3, 2, 77, 136, 520, 1, 0, "bf16", 6),
+    (1, 2, 300, 512, 768, 1, 0, "bf16", 7),
+    (2, 3, 230, 264, 1040, 2, 0, "bf16", 7),
+    (3, 2, 77, 136, 520, 1, 0, "bf16", 7),
     (2, 2, 150, 256, 512, 2, 1, "bf16", 5),
     (4, 2, 70, 136, 520, 1, 0, "bf16", 1),
     (1, 1, 1, 8, 8, 1, 0, "bf16", 1),
