@@ -116,16 +116,21 @@ int moe_dispatch(const void* x, int dtype, int64_t S, int M, int E, int k, int64
  *                        n_src*C rows X[:, g, :, :]
  *   W1 [G, M, H], W2 [G, H, M]  full tensors; the shard uses columns / rows
  *                        [esp_idx*H_l, (esp_idx+1)*H_l), H_l = H/n_esp
- *   Z  [n_src, G, C, H_l] out: pre-activation X*W1 (saved for backward), dtype
- *   Y  [n_src, G, C, M]   out: GeLU(Z)*W2 -- a partial sum when n_esp > 1
+ *   Z  [n_src, G, C, H_l] out: pre-activation X*W1, dtype          } both saved for backward
+ *   A  [n_src, G, C, H_l] out: activation GeLU(Z), dtype           } (the caller owns them)
+ *   Y  [n_src, G, C, M]   out: A*W2 -- a partial sum when n_esp > 1
+ * In bf16 the GeLU and its derivative are evaluated by odd minimax polynomials of the normal CDF
+ * (absolute error below 5e-5 resp. 2e-4, under the bf16 rounding of the stored result); fp32
+ * uses erff.
  *
- * Backward (chain rule of the above), given dY [n_src,G,C,M] and the saved Z:
+ * Backward (chain rule of the above), given dY [n_src,G,C,M] and the saved Z and A:
  *   dX  [n_src, G, C, M]  out
  *   dW1 [G, M, H], dW2 [G, H, M]  FULL tensors; only the shard's columns / rows are written
  *                        (overwritten, dtype, fp32 accumulation over all n_src*C rows)
  * --------------------------------------------------------------------------------------- */
-size_t moe_ffn_workspace_bytes(int dtype, int n_src, int G, int64_t C, int M, int H, int n_esp,
-                               int backward);
+/* Scratch the backward call needs (the gradient of the pre-activation, [n_src,G,C,H_l]); the
+ * forward call needs none.  0 for invalid shapes. */
+size_t moe_ffn_workspace_bytes(int dtype, int n_src, int G, int64_t C, int M, int H, int n_esp);
 
 /* Tuning knob for the bf16 grouped GEMMs.  0 = choose per GEMM from its tile count (default);
  * 1 = 128x128 tiles, register-staged; 2 = 256x256 LDS-DMA kernel with 4 waves; 6 = the same
@@ -137,10 +142,10 @@ int moe_ffn_set_tile(int tile);
 
 int moe_expert_ffn_fwd(const void* X, int dtype, const void* W1, const void* W2,
                        int n_src, int G, int64_t C, int M, int H, int esp_idx, int n_esp,
-                       void* Z, void* Y, void* ws, size_t ws_bytes, void* stream);
+                       void* Z, void* A, void* Y, void* stream);
 
-int moe_expert_ffn_bwd(const void* dY, const void* X, const void* Z, const void* W1,
-                       const void* W2, int dtype,
+int moe_expert_ffn_bwd(const void* dY, const void* X, const void* Z, const void* A,
+                       const void* W1, const void* W2, int dtype,
                        int n_src, int G, int64_t C, int M, int H, int esp_idx, int n_esp,
                        void* dX, void* dW1, void* dW2, void* ws, size_t ws_bytes, void* stream);
 

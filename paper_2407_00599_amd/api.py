@@ -49,14 +49,14 @@ def lib() -> ctypes.CDLL:
         L.moe_dispatch.restype = c_i
         L.moe_dispatch.argtypes = [c_p, c_i, c_i64, c_i, c_i, c_i, c_i64, c_p, c_p, c_p, c_p]
         L.moe_ffn_workspace_bytes.restype = c_sz
-        L.moe_ffn_workspace_bytes.argtypes = [c_i, c_i, c_i, c_i64, c_i, c_i, c_i, c_i]
+        L.moe_ffn_workspace_bytes.argtypes = [c_i, c_i, c_i, c_i64, c_i, c_i, c_i]
         L.moe_ffn_set_tile.restype = c_i
         L.moe_ffn_set_tile.argtypes = [c_i]
         L.moe_expert_ffn_fwd.restype = c_i
         L.moe_expert_ffn_fwd.argtypes = [c_p, c_i, c_p, c_p, c_i, c_i, c_i64, c_i, c_i, c_i, c_i,
-                                         c_p, c_p, c_p, c_sz, c_p]
+                                         c_p, c_p, c_p, c_p]
         L.moe_expert_ffn_bwd.restype = c_i
-        L.moe_expert_ffn_bwd.argtypes = [c_p, c_p, c_p, c_p, c_p, c_i, c_i, c_i, c_i64, c_i, c_i, c_i, c_i,
+        L.moe_expert_ffn_bwd.argtypes = [c_p, c_p, c_p, c_p, c_p, c_p, c_i, c_i, c_i, c_i64, c_i, c_i, c_i, c_i,
                                          c_p, c_p, c_p, c_p, c_sz, c_p]
         L.moe_combine_fwd.restype = c_i
         L.moe_combine_fwd.argtypes = [c_p, c_i, c_i, c_i64, c_i, c_i, c_i, c_i64, c_p, c_p, c_p, c_p, c_p]
@@ -123,8 +123,8 @@ def moe_gate_workspace_bytes(S, E, k) -> int:
     return int(lib().moe_gate_workspace_bytes(S, E, k))
 
 
-def moe_ffn_workspace_bytes(dtype, n_src, G, C, M, H, n_esp, backward) -> int:
-    return int(lib().moe_ffn_workspace_bytes(dtype, n_src, G, C, M, H, n_esp, int(backward)))
+def moe_ffn_workspace_bytes(dtype, n_src, G, C, M, H, n_esp) -> int:
+    return int(lib().moe_ffn_workspace_bytes(dtype, n_src, G, C, M, H, n_esp))
 
 
 def moe_gate_bwd_workspace_bytes(S, M, E) -> int:
@@ -149,15 +149,14 @@ def moe_dispatch(x, S, M, E, k, C, inv, w, buf):
            "moe_dispatch")
 
 
-def moe_expert_ffn_fwd(X, W1, W2, n_src, G, C, M, H, esp_idx, n_esp, Z, Y, ws):
-    wp, wb = _ws_args(ws)
+def moe_expert_ffn_fwd(X, W1, W2, n_src, G, C, M, H, esp_idx, n_esp, Z, A, Y):
     _check(lib().moe_expert_ffn_fwd(_ptr(X), dtype_code(X), _ptr(W1), _ptr(W2), n_src, G, C, M, H, esp_idx, n_esp,
-                                    _ptr(Z), _ptr(Y), wp, wb, _stream()), "moe_expert_ffn_fwd")
+                                    _ptr(Z), _ptr(A), _ptr(Y), _stream()), "moe_expert_ffn_fwd")
 
 
-def moe_expert_ffn_bwd(dY, X, Z, W1, W2, n_src, G, C, M, H, esp_idx, n_esp, dX, dW1, dW2, ws):
+def moe_expert_ffn_bwd(dY, X, Z, A, W1, W2, n_src, G, C, M, H, esp_idx, n_esp, dX, dW1, dW2, ws):
     wp, wb = _ws_args(ws)
-    _check(lib().moe_expert_ffn_bwd(_ptr(dY), _ptr(X), _ptr(Z), _ptr(W1), _ptr(W2), dtype_code(X),
+    _check(lib().moe_expert_ffn_bwd(_ptr(dY), _ptr(X), _ptr(Z), _ptr(A), _ptr(W1), _ptr(W2), dtype_code(X),
                                     n_src, G, C, M, H, esp_idx, n_esp, _ptr(dX), _ptr(dW1), _ptr(dW2),
                                     wp, wb, _stream()), "moe_expert_ffn_bwd")
 

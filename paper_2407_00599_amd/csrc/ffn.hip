@@ -42,7 +42,7 @@ struct GemmArgs {
   const void* A;
   const void* B;
   void* C;
-  void* C2;         // second output (Act) for EPI_GELU / EPI_DGELU
+  void* C2;         // second output (the activation GeLU(Z)) for EPI_GELU
   const void* Zin;  // saved pre-activation for EPI_DGELU
   int G, n_src;
   int Cc;           // rows per chunk (capacity C)
@@ -133,20 +133,36 @@ __device__ __forceinline__ uint4 ldb16(__amdgpu_buffer_rsrc_t r, uint32_t byte_o
   return make_uint4(v.x, v.y, v.z, v.w);
 }
 
-// erf by the rational approximation 7.1.26 of Abramowitz & Stegun (|error| < 1.5e-7), written
-// so that Phi(z) has no cancellation for negative z.  One exp serves GeLU and its derivative.
-__device__ __forceinline__ void gelu_fast(float z, float& g, float& dg) {
-  const float x = __builtin_fabsf(z) * 0.70710678118654752440f;
-  const float t = __builtin_amdgcn_rcpf(fmaf(0.3275911f, x, 1.0f));          // v_rcp_f32
-  const float ex = __builtin_amdgcn_exp2f(x * x * -1.4426950408889634f);      // exp(-x^2) = exp(-z^2/2), v_exp_f32
-  float poly = fmaf(1.061405429f, t, -1.453152027f);
-  poly = fmaf(poly, t, 1.421413741f);
-  poly = fmaf(poly, t, -0.284496736f);
-  poly = fmaf(poly, t, 0.254829592f);
-  const float tail = (0.5f * t) * (poly * ex);    // = 1 - Phi(|z|)
-  const float cdf = z >= 0.f ? 1.0f - tail : tail;
-  g = z * cdf;
-  dg = fmaf(z * 0.39894228040143267794f, ex, cdf);
+// coefficients written by fit_gelu_poly.py (this directory)
+__device__ constexpr float GELU_PHI[9] = {3.989023268e-01f, -6.634449214e-02f, 9.815968573e-03f, -1.108560129e-03f,
+                                          9.341852274e-05f, -5.626405255e-06f, 2.255412426e-07f, -5.327701835e-09f,
+                                          5.564777111e-11f};
+__device__ constexpr float GELU_DG[10] = {7.977564335e-01f, -2.653926015e-01f, 5.909253657e-02f, -9.040454403e-03f,
+                                          9.965471691e-04f, -7.936266047e-05f, 4.432653895e-06f, -1.634905260e-07f,
+                                          3.552443228e-09f, -3.426744305e-11f};
+// GeLU pieces for the bf16 epilogues, transcendental-free: on |z| <= 4.25 the odd parts of
+//   Phi(z) - 1/2            (Phi = standard normal CDF, GeLU(z) = z Phi(z))   and
+//   GeLU'(z) - 1/2 = Phi(z) + z phi(z) - 1/2
+// are odd minimax polynomials in z (9 and 10 coefficients, fitted in fp64 and evaluated by Horner in
+// fp32); outside that range z is clamped, where both functions are within 2e-4 of their limits.
+// Evaluated in fp32: |GeLU error| < 5e-5 (relative 1e-5 for large z), |GeLU' error| < 1.7e-4, both far
+// below the bf16 rounding of the stored result (2^-9 relative).
+__device__ __forceinline__ float gelu_poly(float z) {
+  const float zc = __builtin_amdgcn_fmed3f(z, -4.25f, 4.25f);
+  const float u = zc * zc;
+  float q = fmaf(GELU_PHI[8], u, GELU_PHI[7]);
+#pragma unroll
+  for (int i = 6; i >= 0; --i) q = fmaf(q, u, GELU_PHI[i]);
+  const float cdf = __builtin_amdgcn_fmed3f(fmaf(zc, q, 0.5f), 0.0f, 1.0f);
+  return z * cdf;
+}
+__device__ __forceinline__ float gelu_grad_poly(float z) {
+  const float zc = __builtin_amdgcn_fmed3f(z, -4.25f, 4.25f);
+  const float u = zc * zc;
+  float q = fmaf(GELU_DG[9], u, GELU_DG[8]);
+#pragma unroll
+  for (int i = 7; i >= 0; --i) q = fmaf(q, u, GELU_DG[i]);
+  return fmaf(zc, q, 0.5f);
 }
 
 // Epilogue shared by the bf16 kernels.  A lane holds, for each 32x32 block (i, j) of its wave
@@ -178,24 +194,16 @@ __device__ __forceinline__ void store_tile(const GemmArgs& p, f32x16_t (&acc)[MB
           *reinterpret_cast<uint2*>(Cb + crow + n) = make_uint2(pack_bf16x2(v[0], v[1]), pack_bf16x2(v[2], v[3]));
           float a[4];
 #pragma unroll
-          for (int e = 0; e < 4; ++e) {
-            float dg;
-            gelu_fast(v[e], a[e], dg);
-          }
+          for (int e = 0; e < 4; ++e) a[e] = gelu_poly(v[e]);
           *reinterpret_cast<uint2*>(C2b + crow + n) = make_uint2(pack_bf16x2(a[0], a[1]), pack_bf16x2(a[2], a[3]));
         } else {
           const uint2 zq = *reinterpret_cast<const uint2*>(Zb + crow + n);
           const float z[4] = {__uint_as_float(zq.x << 16), __uint_as_float(zq.x & 0xFFFF0000u),
                               __uint_as_float(zq.y << 16), __uint_as_float(zq.y & 0xFFFF0000u)};
-          float a[4], d[4];
+          float d[4];
 #pragma unroll
-          for (int e = 0; e < 4; ++e) {
-            float dg;
-            gelu_fast(z[e], a[e], dg);
-            d[e] = v[e] * dg;
-          }
+          for (int e = 0; e < 4; ++e) d[e] = v[e] * gelu_grad_poly(z[e]);
           *reinterpret_cast<uint2*>(Cb + crow + n) = make_uint2(pack_bf16x2(d[0], d[1]), pack_bf16x2(d[2], d[3]));
-          *reinterpret_cast<uint2*>(C2b + crow + n) = make_uint2(pack_bf16x2(a[0], a[1]), pack_bf16x2(a[2], a[3]));
         }
       }
     }
@@ -507,7 +515,14 @@ __global__ __launch_bounds__(WM * WN * 64) void ffn_gemm_bf16(const GemmArgs p) 
 // 8-byte pieces strided across 32 rows).  Each wave owns a private slice of the (now idle) stage
 // memory: per 32-row block it writes bf16 results in [32][CW] row-major form (CW = columns of the
 // wave tile, row pitch 2 CW + 16 bytes), reads them back row-wise and stores them; the GeLU
-// epilogues stage their second output, and the saved pre-activation they read, the same way.
+// epilogue stages its second output, and the GeLU' epilogue the saved pre-activation it reads, the
+// same way.  Global memory is addressed through buffer descriptors with 32-bit byte offsets, so
+// the code is branch-free: a row or column outside the problem gets an out-of-range offset, which
+// the hardware drops (stores) or answers with zeros (loads).
+__device__ __forceinline__ void stb16(__amdgpu_buffer_rsrc_t r, uint32_t byte_off, const uint4& v) {
+  const u32x4_t q = {v.x, v.y, v.z, v.w};
+  __builtin_amdgcn_raw_buffer_store_b128(q, r, (int)byte_off, 0, 0);
+}
 template <int KIND, int EPI, int MB, int NBK>
 __device__ __forceinline__ void store_tile_lds(const GemmArgs& p, f32x16_t (&acc)[MB][NBK], char* wave_lds, int g,
                                                int mbase, int nbase, int lane) {
@@ -517,36 +532,72 @@ __device__ __forceinline__ void store_tile_lds(const GemmArgs& p, f32x16_t (&acc
   constexpr int LPR = CW / 8;             // lanes per row in the row-wise phase (16 bytes each)
   constexpr int RPI = 64 / LPR;           // rows per instruction
   constexpr int NT_ = 32 / RPI;           // instructions per 32-row block
-  bf16_t* __restrict__ Cb = reinterpret_cast<bf16_t*>(p.C);
-  bf16_t* __restrict__ C2b = reinterpret_cast<bf16_t*>(p.C2);
-  const bf16_t* __restrict__ Zb = reinterpret_cast<const bf16_t*>(p.Zin);
   char* buf0 = wave_lds;          // first output (or staged Z on the way in)
   char* buf1 = wave_lds + BUF;    // second output
   const int rl = lane / LPR;      // row-wise phase: row RPI t + rl, 16-byte chunk lane % LPR
   const int cc = lane % LPR;
   const int ncol = nbase + cc * 8;
   const bool col_ok = ncol < p.Ndim;
+
+  // descriptors: the activation tensors as a whole, or (weight gradients) this expert's matrix from
+  // the first element of the shard on
+  __amdgpu_buffer_rsrc_t rC, rC2, rZ;
+  if (KIND == KIND_TN) {
+    const uint32_t bytes = (uint32_t)(((int64_t)(p.Mdim - 1) * p.ldc + p.Ndim) * 2);
+    rC = make_rsrc(reinterpret_cast<bf16_t*>(p.C) + ((int64_t)g * p.c_goff + p.c_off), bytes);
+    rC2 = rC; rZ = rC;
+  } else {
+    const uint32_t bytes = (uint32_t)((uint64_t)p.n_src * p.G * p.Cc * (uint64_t)p.ldc * 2);
+    rC = make_rsrc(p.C, bytes);
+    rC2 = make_rsrc(EPI == EPI_GELU ? p.C2 : p.C, bytes);
+    rZ = make_rsrc(EPI == EPI_DGELU ? p.Zin : p.C, bytes);
+  }
+  // byte offset of (row, ncol) for the rows this lane touches in the row-wise phase, or OOB
+  uint32_t off[MB][NT_];
+  if (KIND == KIND_TN) {
+#pragma unroll
+    for (int i = 0; i < MB; ++i)
+#pragma unroll
+      for (int t = 0; t < NT_; ++t) {
+        const int m = mbase + i * 32 + RPI * t + rl;
+        off[i][t] = (m < p.Mdim && col_ok) ? ((uint32_t)m * (uint32_t)p.ldc + (uint32_t)ncol) * 2u : OOB;
+      }
+  } else {
+    // virtual row r of expert g is physical row ((r / C) G + g) C + r % C; one division for the
+    // wave tile, then a compare per row (a wave tile crosses at most one chunk boundary if C is not
+    // smaller than its height)
+    const int q0 = mbase / p.Cc, r0 = mbase - q0 * p.Cc;
+    if (p.Cc >= 32 * MB) {
+#pragma unroll
+      for (int i = 0; i < MB; ++i)
+#pragma unroll
+        for (int t = 0; t < NT_; ++t) {
+          const int d = i * 32 + RPI * t + rl;
+          int rr = r0 + d;
+          const bool wrap = rr >= p.Cc;
+          rr -= wrap ? p.Cc : 0;
+          const uint32_t row = (uint32_t)(((q0 + (wrap ? 1 : 0)) * p.G + g) * p.Cc + rr);
+          off[i][t] = (mbase + d < p.Mdim && col_ok) ? (row * (uint32_t)p.ldc + (uint32_t)ncol) * 2u : OOB;
+        }
+    } else {
+#pragma unroll
+      for (int i = 0; i < MB; ++i)
+#pragma unroll
+        for (int t = 0; t < NT_; ++t) {
+          const int m = mbase + i * 32 + RPI * t + rl;
+          const uint32_t row = (uint32_t)phys_row(m < p.Mdim ? m : 0, g, p.G, p.Cc);
+          off[i][t] = (m < p.Mdim && col_ok) ? (row * (uint32_t)p.ldc + (uint32_t)ncol) * 2u : OOB;
+        }
+    }
+  }
   // accumulator phase: row lane % 32, for block j and q4: 4 columns at 32 j + 8 q4 + 4 (lane / 32)
   const int acc_off = (lane & 31) * PITCH_B + (lane >> 5) * 8;
 #pragma unroll
   for (int i = 0; i < MB; ++i) {
-    int64_t crow[NT_];  // global row offsets of the rows this lane touches in the row-wise phase
-    bool row_ok[NT_];
-#pragma unroll
-    for (int t = 0; t < NT_; ++t) {
-      const int m = mbase + i * 32 + RPI * t + rl;
-      row_ok[t] = m < p.Mdim;
-      const int mm = row_ok[t] ? m : 0;
-      if (KIND == KIND_TN) crow[t] = (int64_t)g * p.c_goff + p.c_off + (int64_t)mm * p.ldc;
-      else crow[t] = phys_row(mm, g, p.G, p.Cc) * p.ldc;
-    }
     if (EPI == EPI_DGELU) {  // bring in the saved pre-activation, row-wise
 #pragma unroll
-      for (int t = 0; t < NT_; ++t) {
-        uint4 z = make_uint4(0, 0, 0, 0);
-        if (row_ok[t] && col_ok) z = *reinterpret_cast<const uint4*>(Zb + crow[t] + ncol);
-        *reinterpret_cast<uint4*>(buf0 + (RPI * t + rl) * PITCH_B + cc * 16) = z;
-      }
+      for (int t = 0; t < NT_; ++t)
+        *reinterpret_cast<uint4*>(buf0 + (RPI * t + rl) * PITCH_B + cc * 16) = ldb16(rZ, off[i][t]);
     }
 #pragma unroll
     for (int j = 0; j < NBK; ++j) {
@@ -560,37 +611,26 @@ __device__ __forceinline__ void store_tile_lds(const GemmArgs& p, f32x16_t (&acc
         } else if (EPI == EPI_GELU) {
           float a[4];
 #pragma unroll
-          for (int e = 0; e < 4; ++e) {
-            float dg;
-            gelu_fast(v[e], a[e], dg);
-          }
+          for (int e = 0; e < 4; ++e) a[e] = gelu_poly(v[e]);
           *reinterpret_cast<uint2*>(a0) = make_uint2(pack_bf16x2(v[0], v[1]), pack_bf16x2(v[2], v[3]));
           *reinterpret_cast<uint2*>(a1) = make_uint2(pack_bf16x2(a[0], a[1]), pack_bf16x2(a[2], a[3]));
         } else {
           const uint2 zq = *reinterpret_cast<const uint2*>(a0);
           const float z[4] = {__uint_as_float(zq.x << 16), __uint_as_float(zq.x & 0xFFFF0000u),
                               __uint_as_float(zq.y << 16), __uint_as_float(zq.y & 0xFFFF0000u)};
-          float a[4], d[4];
+          float d[4];
 #pragma unroll
-          for (int e = 0; e < 4; ++e) {
-            float dg;
-            gelu_fast(z[e], a[e], dg);
-            d[e] = v[e] * dg;
-          }
+          for (int e = 0; e < 4; ++e) d[e] = v[e] * gelu_grad_poly(z[e]);
           *reinterpret_cast<uint2*>(a0) = make_uint2(pack_bf16x2(d[0], d[1]), pack_bf16x2(d[2], d[3]));
-          *reinterpret_cast<uint2*>(a1) = make_uint2(pack_bf16x2(a[0], a[1]), pack_bf16x2(a[2], a[3]));
         }
       }
     }
     // row-wise read-back and store (LDS operations of one wave complete in program order)
 #pragma unroll
     for (int t = 0; t < NT_; ++t) {
-      const uint4 o0 = *reinterpret_cast<const uint4*>(buf0 + (RPI * t + rl) * PITCH_B + cc * 16);
-      if (row_ok[t] && col_ok) *reinterpret_cast<uint4*>(Cb + crow[t] + ncol) = o0;
-      if (EPI != EPI_STORE) {
-        const uint4 o1 = *reinterpret_cast<const uint4*>(buf1 + (RPI * t + rl) * PITCH_B + cc * 16);
-        if (row_ok[t] && col_ok) *reinterpret_cast<uint4*>(C2b + crow[t] + ncol) = o1;
-      }
+      stb16(rC, off[i][t], *reinterpret_cast<const uint4*>(buf0 + (RPI * t + rl) * PITCH_B + cc * 16));
+      if (EPI == EPI_GELU)
+        stb16(rC2, off[i][t], *reinterpret_cast<const uint4*>(buf1 + (RPI * t + rl) * PITCH_B + cc * 16));
     }
   }
 }
@@ -621,7 +661,9 @@ typedef short s16x4_t __attribute__((ext_vector_type(4)));
 
 constexpr int DT = 256;                    // tile edge
 constexpr int DK = 32;                     // k tile
-constexpr int DSTAGES = 4;
+constexpr int DSTAGES = 5;                 // 160 KiB: all of a compute unit's LDS
+// s_waitcnt immediate that waits until at most n vector-memory operations are outstanding (gfx9 encoding)
+constexpr int vmcnt_imm(int n) { return 0x0F70 | (n & 15) | ((n >> 4) << 14); }
 constexpr int DREGION = DT * DK * 2;       // bytes per operand per stage (16 KiB)
 constexpr int DSTAGE = 2 * DREGION;
 
@@ -714,8 +756,8 @@ __global__ __launch_bounds__(128 * WN) void ffn_gemm_dma(const GemmArgs p) {
   // Requests of k tile kt into its stage, one instruction (1 KiB) at a time: which = 0 (A) / 1 (B),
   // j = 0..RPW-1.  Tiles past the end still issue (all lanes out of range, zeros are written) so that
   // the number of outstanding requests per wave is the same in every iteration.
-  auto request1 = [&](int kt, int which, int j) {
-    char* st = smem + (kt & (DSTAGES - 1)) * DSTAGE;
+  auto request1 = [&](int kt, int stage, int which, int j) {
+    char* st = smem + stage * DSTAGE;
     const bool live = kt < nk;
     uint32_t add;   // byte offset of the k tile
     int lim;        // valid k count in this tile
@@ -736,9 +778,9 @@ __global__ __launch_bounds__(128 * WN) void ffn_gemm_dma(const GemmArgs p) {
       dma16(rB, reinterpret_cast<bf16_t*>(st + DREGION + q * 1024),
             (b_req[j] != OOB && b_k[j] < lim) ? b_req[j] + add : OOB);
   };
-  auto request_half = [&](int kt, int which) {
+  auto request_half = [&](int kt, int which) {   // prologue only: kt < DSTAGES
 #pragma unroll
-    for (int j = 0; j < RPW; ++j) request1(kt, which, j);
+    for (int j = 0; j < RPW; ++j) request1(kt, kt, which, j);
   };
 
   // ---- per-lane fragment addresses inside a stage (bytes), for k step kk = 0; kk = 1 adds a constant ----
@@ -781,9 +823,9 @@ __global__ __launch_bounds__(128 * WN) void ffn_gemm_dma(const GemmArgs p) {
   const uint32_t lds0 = (uint32_t)(uintptr_t)(LDS_AS char*)smem;
   // fragments of k step kk of tile kt go to register set kk; part 0 = the four B fragments,
   // part 1 = A fragments 0,1, part 2 = A fragments 2,3 (so the reads can be spread between MFMAs)
-  auto load_frags = [&](int kt, auto kk_tag, int part) {
+  auto load_frags = [&](int stage, auto kk_tag, int part) {
     constexpr int kk = decltype(kk_tag)::value;
-    const uint32_t st = lds0 + (uint32_t)(kt & (DSTAGES - 1)) * DSTAGE;
+    const uint32_t st = lds0 + (uint32_t)stage * DSTAGE;
     if (part == 0) {
       if (!B_NC) {
         lds_read_kc<0 * 2048>(fb[kk][0], st + b_fr[kk][0]); lds_read_kc<1 * 2048>(fb[kk][1], st + b_fr[kk][0]);
@@ -835,9 +877,10 @@ __global__ __launch_bounds__(128 * WN) void ffn_gemm_dma(const GemmArgs p) {
 
   request_half(0, 0); request_half(0, 1);
   request_half(1, 0); request_half(1, 1);
-  request_half(2, 0);
-  // vmcnt(3 RPW): this wave's requests for tile 0 have landed
-  __builtin_amdgcn_s_waitcnt(RPW == 4 ? 0x0F7C : 0x0F76);
+  request_half(2, 0); request_half(2, 1);
+  request_half(3, 0);
+  // this wave's requests for tile 0 have landed (the 5 RPW issued after them may be in flight)
+  __builtin_amdgcn_s_waitcnt(vmcnt_imm(5 * RPW));
   __builtin_amdgcn_s_barrier();
   load_frags(0, K0{}, 0); load_frags(0, K0{}, 1); load_frags(0, K0{}, 2);
 
@@ -846,10 +889,13 @@ __global__ __launch_bounds__(128 * WN) void ffn_gemm_dma(const GemmArgs p) {
     for (int j = 0; j < NBK; ++j)
       acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[set][j].v, fa[set][i].v, acc[i][j], 0, 0, 0);
   };
-  // Each k tile is two MFMA steps of four rows (NBK MFMAs each).  Between the rows go, one piece at
+  auto next_stage = [](int s_) { return s_ + 1 == DSTAGES ? 0 : s_ + 1; };
+  // Each k tile is two MFMA steps of MB rows (NBK MFMAs each).  Between the rows go, one piece at
   // a time, the fragment reads of the next step and the tile requests, so that neither the LDS nor
   // the address path sees a burst and the matrix pipe always has work queued.
-  //   step 0: B-operand requests of tile kt+2;  step 1: barrier, then A-operand requests of tile kt+3
+  //   step 0: B-operand requests of tile kt+3;  step 1: barrier, then A-operand requests of tile kt+4
+  // (stage of tile t = t mod 5: s0 holds tile kt, s1 tile kt+1, s3 tile kt+3, s4 tile kt+4 = the stage of kt-1)
+  int s0 = 0, s1 = 1, s3 = 3, s4 = 4;
   for (int kt = 0; kt < nk; ++kt) {
     frags_ready(0);
     __builtin_amdgcn_sched_barrier(0);
@@ -857,28 +903,29 @@ __global__ __launch_bounds__(128 * WN) void ffn_gemm_dma(const GemmArgs p) {
     for (int i = 0; i < MB; ++i) {
       mfma_row(0, i);
       __builtin_amdgcn_sched_barrier(0);
-      if (i < 3) load_frags(kt, K1{}, i);
-      if (i < RPW) request1(kt + 2, 1, i);
+      if (i < 3) load_frags(s0, K1{}, i);
+      if (i < RPW) request1(kt + 3, s3, 1, i);
       __builtin_amdgcn_sched_barrier(0);
     }
     frags_ready(1);
     __builtin_amdgcn_sched_barrier(0);
     mfma_row(1, 0);
     __builtin_amdgcn_sched_barrier(0);
-    // vmcnt(2 RPW): tile kt+1 has landed (the requests of tile kt+2 may still be in flight)
-    __builtin_amdgcn_s_waitcnt(RPW == 4 ? 0x0F78 : 0x0F74);
+    // tile kt+1 has landed (the 4 RPW requests of tiles kt+2, kt+3 issued after it may still be in flight)
+    __builtin_amdgcn_s_waitcnt(vmcnt_imm(4 * RPW));
     __builtin_amdgcn_s_barrier();        // everyone is past tile kt-1, and tile kt+1 is complete
     __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
     for (int i = 1; i < MB; ++i) {
-      load_frags(kt + 1, K0{}, i - 1);
-      if (MB == 3 && i == 2) load_frags(kt + 1, K0{}, 2);
-      if (i - 1 < RPW) request1(kt + 3, 0, i - 1);
+      load_frags(s1, K0{}, i - 1);
+      if (MB == 3 && i == 2) load_frags(s1, K0{}, 2);
+      if (i - 1 < RPW) request1(kt + 4, s4, 0, i - 1);
       __builtin_amdgcn_sched_barrier(0);
       mfma_row(1, i);
       __builtin_amdgcn_sched_barrier(0);
     }
-    if (RPW == 4) request1(kt + 3, 0, 3);
+    if (RPW == 4) request1(kt + 4, s4, 0, 3);
+    s0 = s1; s1 = next_stage(s1); s3 = next_stage(s3); s4 = next_stage(s4);
   }
   __builtin_amdgcn_s_waitcnt(0x0070);  // drain trailing (empty) requests and fragment reads before LDS is released
 
@@ -976,7 +1023,6 @@ __global__ __launch_bounds__(256) void ffn_gemm_f32(const GemmArgs p) {
         float ge, dg;
         gelu_and_grad(Z[crow + n], ge, dg);
         C[crow + n] = v * dg;
-        C2[crow + n] = ge;
       }
     }
   }
@@ -1064,37 +1110,32 @@ extern "C" int moe_ffn_set_tile(int tile) {
   return MOE_OK;
 }
 
-extern "C" size_t moe_ffn_workspace_bytes(int dtype, int n_src, int G, int64_t C, int M, int H, int n_esp,
-                                          int backward) {
+extern "C" size_t moe_ffn_workspace_bytes(int dtype, int n_src, int G, int64_t C, int M, int H, int n_esp) {
   if (check_ffn_shape(dtype, n_src, G, C, M, H, 0, n_esp) != MOE_OK) return 0;
   const size_t esz = dtype == MOE_BF16 ? 2 : 4;
-  const size_t one = moe::align_up((size_t)n_src * G * C * (size_t)(H / n_esp) * esz, 256);
-  return backward ? 2 * one : one;
+  return moe::align_up((size_t)n_src * G * C * (size_t)(H / n_esp) * esz, 256);   // dZ
 }
 
 extern "C" int moe_expert_ffn_fwd(const void* X, int dtype, const void* W1, const void* W2, int n_src, int G,
-                                  int64_t C, int M, int H, int esp_idx, int n_esp, void* Z, void* Y, void* ws,
-                                  size_t ws_bytes, void* stream) {
+                                  int64_t C, int M, int H, int esp_idx, int n_esp, void* Z, void* A, void* Y,
+                                  void* stream) {
   if (int rc = check_ffn_shape(dtype, n_src, G, C, M, H, esp_idx, n_esp)) return rc;
-  MOE_REQUIRE_PTR(X); MOE_REQUIRE_PTR(W1); MOE_REQUIRE_PTR(W2); MOE_REQUIRE_PTR(Z); MOE_REQUIRE_PTR(Y);
-  const size_t need = moe_ffn_workspace_bytes(dtype, n_src, G, C, M, H, n_esp, 0);
-  MOE_REQUIRE(ws != nullptr && ws_bytes >= need, MOE_EWORKSPACE);
-  MOE_REQUIRE(moe::aligned16(ws), MOE_EALIGN);
+  MOE_REQUIRE_PTR(X); MOE_REQUIRE_PTR(W1); MOE_REQUIRE_PTR(W2); MOE_REQUIRE_PTR(Z); MOE_REQUIRE_PTR(A);
+  MOE_REQUIRE_PTR(Y);
   hipStream_t st = (hipStream_t)stream;
   const int Hl = H / n_esp;
   const int64_t h0 = (int64_t)esp_idx * Hl;
-  void* Act = ws;
 
   GemmArgs a{};
   a.G = G; a.n_src = n_src; a.Cc = (int)C; a.R = (int)(n_src * C);
-  // Z = X * W1[:, h0:h0+Hl]; Act = GeLU(Z)
+  // Z = X * W1[:, h0:h0+Hl] ; A = GeLU(Z)
   a.A = X; a.lda = M;
   a.B = W1; a.ldb = H; a.b_goff = (int64_t)M * H; a.b_off = h0;
-  a.C = Z; a.C2 = Act; a.ldc = Hl;
+  a.C = Z; a.C2 = A; a.ldc = Hl;
   a.Mdim = a.R; a.Ndim = Hl; a.Kdim = M;
   launch_gemm<KIND_NN, EPI_GELU>(a, dtype, st);
-  // Y = Act * W2[h0:h0+Hl, :]
-  a.A = Act; a.lda = Hl;
+  // Y = A * W2[h0:h0+Hl, :]
+  a.A = A; a.lda = Hl;
   a.B = W2; a.ldb = M; a.b_goff = (int64_t)H * M; a.b_off = h0 * M;
   a.C = Y; a.C2 = nullptr; a.ldc = M;
   a.Mdim = a.R; a.Ndim = M; a.Kdim = Hl;
@@ -1102,27 +1143,27 @@ extern "C" int moe_expert_ffn_fwd(const void* X, int dtype, const void* W1, cons
   return moe::check_launch();
 }
 
-extern "C" int moe_expert_ffn_bwd(const void* dY, const void* X, const void* Z, const void* W1, const void* W2,
-                                  int dtype, int n_src, int G, int64_t C, int M, int H, int esp_idx, int n_esp,
-                                  void* dX, void* dW1, void* dW2, void* ws, size_t ws_bytes, void* stream) {
+extern "C" int moe_expert_ffn_bwd(const void* dY, const void* X, const void* Z, const void* A, const void* W1,
+                                  const void* W2, int dtype, int n_src, int G, int64_t C, int M, int H, int esp_idx,
+                                  int n_esp, void* dX, void* dW1, void* dW2, void* ws, size_t ws_bytes, void* stream) {
   if (int rc = check_ffn_shape(dtype, n_src, G, C, M, H, esp_idx, n_esp)) return rc;
-  MOE_REQUIRE_PTR(dY); MOE_REQUIRE_PTR(X); MOE_REQUIRE_PTR(Z); MOE_REQUIRE_PTR(W1); MOE_REQUIRE_PTR(W2);
-  MOE_REQUIRE_PTR(dX); MOE_REQUIRE_PTR(dW1); MOE_REQUIRE_PTR(dW2);
-  const size_t need = moe_ffn_workspace_bytes(dtype, n_src, G, C, M, H, n_esp, 1);
+  MOE_REQUIRE_PTR(dY); MOE_REQUIRE_PTR(X); MOE_REQUIRE_PTR(Z); MOE_REQUIRE_PTR(A); MOE_REQUIRE_PTR(W1);
+  MOE_REQUIRE_PTR(W2); MOE_REQUIRE_PTR(dX); MOE_REQUIRE_PTR(dW1); MOE_REQUIRE_PTR(dW2);
+  const size_t need = moe_ffn_workspace_bytes(dtype, n_src, G, C, M, H, n_esp);
   MOE_REQUIRE(ws != nullptr && ws_bytes >= need, MOE_EWORKSPACE);
   MOE_REQUIRE(moe::aligned16(ws), MOE_EALIGN);
   hipStream_t st = (hipStream_t)stream;
   const int Hl = H / n_esp;
   const int64_t h0 = (int64_t)esp_idx * Hl;
-  void* Act = ws;
-  void* dZ = (char*)ws + need / 2;
+  const void* Act = A;
+  void* dZ = ws;
 
   GemmArgs a{};
   a.G = G; a.n_src = n_src; a.Cc = (int)C; a.R = (int)(n_src * C);
-  // dA = dY * W2[h0:h0+Hl, :]^T ; dZ = dA * GeLU'(Z) ; Act = GeLU(Z)
+  // dA = dY * W2[h0:h0+Hl, :]^T ; dZ = dA * GeLU'(Z)
   a.A = dY; a.lda = M;
   a.B = W2; a.ldb = M; a.b_goff = (int64_t)H * M; a.b_off = h0 * M;
-  a.C = dZ; a.C2 = Act; a.Zin = Z; a.ldc = Hl;
+  a.C = dZ; a.C2 = nullptr; a.Zin = Z; a.ldc = Hl;
   a.Mdim = a.R; a.Ndim = Hl; a.Kdim = M;
   launch_gemm<KIND_NT, EPI_DGELU>(a, dtype, st);
   // dW2[h0:h0+Hl, :] = Act^T * dY

@@ -30,7 +30,7 @@ class MoERankLayer:
         self.logits = e(S, E, dt=f32); self.idx = e(S, k, dt=i32); self.slot = e(S, k, dt=i32)
         self.w = e(S, k, dt=f32); self.inv = e(E, C, dt=i32); self.counts = e(E, dt=i32)
         self.buf = e(E, C, M)
-        self.Z = e(n_esp, E, C, Hl)
+        self.Z = e(n_esp, E, C, Hl); self.A = e(n_esp, E, C, Hl)
         self.Yret = e(n_esp, E, C, M)
         self.y = e(S, M)
         # backward
@@ -39,7 +39,7 @@ class MoERankLayer:
         self.dW1 = e(E, M, H); self.dW2 = e(E, H, M)
         self.dx = e(S, M); self.dlogits = e(S, E, dt=f32); self.dWg = e(M, E, dt=f32); self.dbias = e(E, dt=f32)
         nbytes = max(api.moe_gate_workspace_bytes(S, E, k),
-                     api.moe_ffn_workspace_bytes(self.dt, 1, E, C, M, H, n_esp, 1),
+                     api.moe_ffn_workspace_bytes(self.dt, 1, E, C, M, H, n_esp),
                      api.moe_gate_bwd_workspace_bytes(S, M, E), 256)
         self.ws = torch.empty(nbytes, dtype=torch.uint8, device=dev)
 
@@ -55,7 +55,7 @@ class MoERankLayer:
         self.gate(x_full, Wg, bias)
         api.moe_dispatch(self.x, S, M, E, k, C, self.inv, None, self.buf)
         for j in range(self.n_esp):           # the N_ESP shards of every expert, one after the other
-            api.moe_expert_ffn_fwd(self.buf, W1, W2, 1, E, C, M, H, j, self.n_esp, self.Z[j], self.Yret[j], self.ws)
+            api.moe_expert_ffn_fwd(self.buf, W1, W2, 1, E, C, M, H, j, self.n_esp, self.Z[j], self.A[j], self.Yret[j])
         api.moe_combine_fwd(self.Yret, self.n_esp, S, M, E, k, C, self.idx, self.slot, self.w, self.y)
         return self.y
 
@@ -64,7 +64,8 @@ class MoERankLayer:
         api.moe_combine_bwd(dy, self.Yret, self.n_esp, S, M, E, k, C, self.idx, self.slot, self.inv, self.w,
                             self.dYret, self.dw)
         for j in range(self.n_esp):
-            api.moe_expert_ffn_bwd(self.dYret, self.buf, self.Z[j], self.W1, self.W2, 1, E, C, M, H, j, self.n_esp,
+            api.moe_expert_ffn_bwd(self.dYret, self.buf, self.Z[j], self.A[j], self.W1, self.W2, 1, E, C, M, H, j,
+                                   self.n_esp,
                                    self.dbuf[j], self.dW1, self.dW2, self.ws)
         # backward of dispatch = unweighted combine of the (n_esp partial) input gradients
         api.moe_combine_fwd(self.dbuf, self.n_esp, S, M, E, k, C, self.idx, self.slot, None, self.dx)
@@ -103,7 +104,7 @@ class MoERankShape:
         self.logits = e(S, E, dt=f32); self.idx = e(S, k, dt=i32); self.slot = e(S, k, dt=i32)
         self.w = e(S, k, dt=f32); self.inv = e(E, C, dt=i32); self.counts = e(E, dt=i32)
         self.buf = e(E, C, M)
-        self.Z = e(n_src, G, C, Hl)
+        self.Z = e(n_src, G, C, Hl); self.A = e(n_src, G, C, Hl)
         self.Yout = e(n_src, G, C, M)
         self.y = e(S, M)
         self.dYret = e(E, C, M); self.dw = e(S, k, dt=f32)
@@ -117,7 +118,7 @@ class MoERankShape:
             self.Xrecv = e(n_src, G, C, M); self.Yret = e(n_esp, E, C, M)
             self.dYrecv = e(n_src, G, C, M); self.dbuf = e(n_esp, E, C, M)
         nbytes = max(api.moe_gate_workspace_bytes(S, E, k),
-                     api.moe_ffn_workspace_bytes(self.dt, n_src, G, C, M, H, n_esp, 1),
+                     api.moe_ffn_workspace_bytes(self.dt, n_src, G, C, M, H, n_esp),
                      api.moe_gate_bwd_workspace_bytes(S, M, E), 256)
         self.ws = torch.empty(nbytes, dtype=torch.uint8, device=dev)
 
@@ -137,7 +138,7 @@ class MoERankShape:
 
     def ffn_fwd(self):
         api.moe_expert_ffn_fwd(self.Xrecv, self.W1, self.W2, self.n_src, self.G, self.C, self.M, self.H, self.esp_idx,
-                               self.n_esp, self.Z, self.Yout, self.ws)
+                               self.n_esp, self.Z, self.A, self.Yout)
 
     def combine(self):
         api.moe_combine_fwd(self.Yret, self.n_esp, self.S, self.M, self.E, self.k, self.C, self.idx, self.slot,
@@ -148,7 +149,7 @@ class MoERankShape:
                             self.slot, self.inv, self.w, self.dYret, self.dw)
 
     def ffn_bwd(self):
-        api.moe_expert_ffn_bwd(self.dYrecv, self.Xrecv, self.Z, self.W1, self.W2, self.n_src, self.G, self.C, self.M,
+        api.moe_expert_ffn_bwd(self.dYrecv, self.Xrecv, self.Z, self.A, self.W1, self.W2, self.n_src, self.G, self.C, self.M,
                                self.H, self.esp_idx, self.n_esp, self.dXout, self.dW1, self.dW2, self.ws)
 
     def dispatch_bwd(self):

@@ -35,7 +35,7 @@ def test_every_declared_symbol_is_exported_and_bound(L):
     for n in names:                       # the Python binding has the same names
         if n not in ("moe_strerror", "moe_abi_version"):
             assert hasattr(api, n), n
-    assert L.moe_abi_version() == 1
+    assert L.moe_abi_version() == 2
 
 
 def test_error_strings(L):
@@ -102,14 +102,14 @@ def test_dispatch_combine_argument_checks(L):
 
 def test_ffn_argument_checks(L):
     f = L.moe_ffn_workspace_bytes
-    assert f(1, 2, 4, 100, 64, 256, 2, 0) == api.moe_ffn_workspace_bytes(1, 2, 4, 100, 64, 256, 2, False)
-    one = f(1, 2, 4, 100, 64, 256, 2, 0)
-    assert one >= 2 * 4 * 100 * 128 * 2 and f(1, 2, 4, 100, 64, 256, 2, 1) == 2 * one
-    assert f(0, 2, 4, 100, 64, 256, 2, 0) >= 2 * 4 * 100 * 128 * 4
-    assert f(1, 2, 4, 100, 64, 250, 4, 0) == 0                 # H % n_esp != 0 -> invalid -> 0
+    assert f(1, 2, 4, 100, 64, 256, 2) == api.moe_ffn_workspace_bytes(1, 2, 4, 100, 64, 256, 2)
+    one = f(1, 2, 4, 100, 64, 256, 2)
+    assert 2 * 4 * 100 * 128 * 2 <= one < 2 * 4 * 100 * 128 * 2 + 256
+    assert f(0, 2, 4, 100, 64, 256, 2) >= 2 * 4 * 100 * 128 * 4
+    assert f(1, 2, 4, 100, 64, 250, 4) == 0                 # H % n_esp != 0 -> invalid -> 0
 
-    def fwd(dt=1, n_src=1, G=2, C=10, M=64, H=128, e=0, n=1, X=A, Z=A, ws=A, wsb=1 << 30):
-        return L.moe_expert_ffn_fwd(X, dt, A, A, n_src, G, C, M, H, e, n, Z, A, ws, wsb, None)
+    def fwd(dt=1, n_src=1, G=2, C=10, M=64, H=128, e=0, n=1, X=A, Z=A, Act=A):
+        return L.moe_expert_ffn_fwd(X, dt, A, A, n_src, G, C, M, H, e, n, Z, Act, A, None)
     assert fwd(H=130, n=4) == -1
     assert fwd(e=2, n=2) == -1
     assert fwd(e=-1) == -1
@@ -119,10 +119,11 @@ def test_ffn_argument_checks(L):
     assert fwd(H=132, n=1) == -2                   # H_l % 8
     assert fwd(X=None) == -6
     assert fwd(Z=U) == -3
-    assert fwd(wsb=16) == -5
-    assert fwd(ws=None) == -5
-    assert L.moe_expert_ffn_bwd(A, A, A, A, A, 1, 1, 2, 10, 64, 128, 0, 1, A, A, None, A, 1 << 30, None) == -6
-    assert L.moe_expert_ffn_bwd(A, A, A, A, A, 1, 1, 2, 10, 64, 128, 0, 1, A, A, A, A, 64, None) == -5
+    assert fwd(Act=None) == -6
+    assert L.moe_expert_ffn_bwd(A, A, A, A, A, A, 1, 1, 2, 10, 64, 128, 0, 1, A, A, None, A, 1 << 30, None) == -6
+    assert L.moe_expert_ffn_bwd(A, A, A, None, A, A, 1, 1, 2, 10, 64, 128, 0, 1, A, A, A, A, 1 << 30, None) == -6
+    assert L.moe_expert_ffn_bwd(A, A, A, A, A, A, 1, 1, 2, 10, 64, 128, 0, 1, A, A, A, A, 64, None) == -5
+    assert L.moe_expert_ffn_bwd(A, A, A, A, A, A, 1, 1, 2, 10, 64, 128, 0, 1, A, A, A, None, 1 << 30, None) == -5
     assert L.moe_ffn_set_tile(8) == -1 and L.moe_ffn_set_tile(-1) == -1 and L.moe_ffn_set_tile(0) == 0
 
 

@@ -20,11 +20,12 @@ def gpu_ffn(X, dY, W1, W2, n_src, G, C, M, H, esp_idx, n_esp, tdt):
     Z = torch.empty(n_src, G, C, Hl, dtype=tdt, device=DEV); Y = torch.empty(n_src, G, C, M, dtype=tdt, device=DEV)
     dX = torch.empty_like(Y)
     dW1 = torch.full((G, M, H), 3.0, dtype=tdt, device=DEV); dW2 = torch.full((G, H, M), 3.0, dtype=tdt, device=DEV)
-    ws = torch.empty(api.moe_ffn_workspace_bytes(dt, n_src, G, C, M, H, n_esp, True), dtype=torch.uint8, device=DEV)
-    api.moe_expert_ffn_fwd(X, W1, W2, n_src, G, C, M, H, esp_idx, n_esp, Z, Y, ws)
-    api.moe_expert_ffn_bwd(dY, X, Z, W1, W2, n_src, G, C, M, H, esp_idx, n_esp, dX, dW1, dW2, ws)
+    A = torch.empty_like(Z)
+    ws = torch.empty(api.moe_ffn_workspace_bytes(dt, n_src, G, C, M, H, n_esp), dtype=torch.uint8, device=DEV)
+    api.moe_expert_ffn_fwd(X, W1, W2, n_src, G, C, M, H, esp_idx, n_esp, Z, A, Y)
+    api.moe_expert_ffn_bwd(dY, X, Z, A, W1, W2, n_src, G, C, M, H, esp_idx, n_esp, dX, dW1, dW2, ws)
     torch.cuda.synchronize()
-    return Z, Y, dX, dW1, dW2
+    return Z, A, Y, dX, dW1, dW2
 
 
 CASES = [
@@ -64,7 +65,7 @@ def test_ffn_fwd_bwd_elementwise(n_src, G, C, M, H, n_esp, esp_idx, dtype, tile)
     W2 = synth.store((rng.standard_normal((G, H, M)) / np.sqrt(H)).astype(np.float32), dtype)
     api.moe_ffn_set_tile(tile)
     try:
-        Z, Y, dX, dW1, dW2 = gpu_ffn(to_dev(X), to_dev(dY), to_dev(W1), to_dev(W2), n_src, G, C, M, H, esp_idx, n_esp, tdt)
+        Z, A, Y, dX, dW1, dW2 = gpu_ffn(to_dev(X), to_dev(dY), to_dev(W1), to_dev(W2), n_src, G, C, M, H, esp_idx, n_esp, tdt)
     finally:
         api.moe_ffn_set_tile(0)
     rZ, rY = O.expert_ffn_fwd(X.val, W1.val, W2.val, esp_idx, n_esp)
@@ -72,6 +73,7 @@ def test_ffn_fwd_bwd_elementwise(n_src, G, C, M, H, n_esp, esp_idx, dtype, tile)
     tol = TOL[dtype]
     Hl = H // n_esp; hs = slice(esp_idx * Hl, (esp_idx + 1) * Hl)
     assert rel_err(to_host(Z), rZ) <= tol
+    assert rel_err(to_host(A), O.gelu(rZ)) <= tol
     assert rel_err(to_host(Y), rY) <= tol
     assert rel_err(to_host(dX), rdX) <= tol
     hW1, hW2 = to_host(dW1), to_host(dW2)
@@ -107,7 +109,7 @@ def test_ffn_full_size_sampled(name):
     C = O.capacity(cfg.S, cfg.E, cfg.k, cfg.f)
     n_src, G, M, H, Hl = cfg.n_src, cfg.G, cfg.M, cfg.H, cfg.H_local
     X, dY, W1, W2 = _device_inputs(cfg, C, cfg.cfg_id)
-    Z, Y, dX, dW1, dW2 = gpu_ffn(X, dY, W1, W2, n_src, G, C, M, H, cfg.esp_idx, cfg.n_esp, torch.bfloat16)
+    Z, A, Y, dX, dW1, dW2 = gpu_ffn(X, dY, W1, W2, n_src, G, C, M, H, cfg.esp_idx, cfg.n_esp, torch.bfloat16)
     hs = slice(cfg.esp_idx * Hl, (cfg.esp_idx + 1) * Hl)
     rng = np.random.default_rng(cfg.cfg_id)
     tol = TOL["bf16"]
@@ -118,6 +120,7 @@ def test_ffn_full_size_sampled(name):
         ss = torch.tensor([p[0] for p in pick], device=DEV); cc = torch.tensor([p[1] for p in pick], device=DEV)
         z, y, dx = O.expert_ffn_rows(to_host(X[ss, g, cc]), to_host(dY[ss, g, cc]), w1s, w2s)
         assert rel_err(to_host(Z[ss, g, cc]), z) <= tol
+        assert rel_err(to_host(A[ss, g, cc]), O.gelu(z)) <= tol
         assert rel_err(to_host(Y[ss, g, cc]), y) <= tol
         assert rel_err(to_host(dX[ss, g, cc]), dx) <= tol
         Xg = to_host(X[:, g].reshape(n_src * C, M)); dYg = to_host(dY[:, g].reshape(n_src * C, M))
