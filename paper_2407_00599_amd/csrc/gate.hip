@@ -208,21 +208,25 @@ __device__ __forceinline__ Cand better(Cand a, Cand b) {
 }
 
 // W lanes per token (W = pow2, W*EPL >= E).  Lane r of a group holds experts r, r+W, ...
+// One block per GATE_TB tokens, min(W, 8) waves: the W passes (GATE_TB / W tokens each) are dealt to the waves.
 template <int W, int EPL>
-__global__ __launch_bounds__(GATE_TB) void gate_topk(const float* __restrict__ logits, int64_t S, int E, int k,
+__global__ __launch_bounds__(GATE_TB * (W < 8 ? W : 8)) void gate_topk(const float* __restrict__ logits, int64_t S, int E, int k,
                                                       int norm_topk, int32_t* __restrict__ idx, float* __restrict__ w,
                                                       int32_t* __restrict__ blockhist) {
   __shared__ int hist[MOE_MAX_K * MOE_MAX_E];
-  const int tid = threadIdx.x;
-  for (int i = tid; i < k * E; i += GATE_TB) hist[i] = 0;
+  constexpr int NWV = W < 8 ? W : 8;   // waves per block
+  constexpr int PPW = W / NWV;         // passes per wave
+  const int tid = threadIdx.x & (GATE_TB - 1), wave = threadIdx.x / GATE_TB;
+  for (int i = threadIdx.x; i < k * E; i += GATE_TB * NWV) hist[i] = 0;
   __syncthreads();
   const int r = tid % W;
   const int64_t tb0 = (int64_t)blockIdx.x * GATE_TB;
   constexpr int TPP = GATE_TB / W;  // tokens per pass
-  constexpr int PG = W < 4 ? W : 4;  // passes whose logits are requested together
+  constexpr int PG = PPW < 4 ? PPW : 4;  // passes whose logits are requested together
   float vv[PG][EPL];
-  for (int pass = 0; pass < W; ++pass) {
-    if (pass % PG == 0) {
+  for (int pi = 0; pi < PPW; ++pi) {
+    const int pass = wave * PPW + pi;
+    if (pi % PG == 0) {
 #pragma unroll
       for (int u = 0; u < PG; ++u) {
         const int64_t tu = tb0 + (pass + u) * TPP + tid / W;
@@ -243,7 +247,7 @@ __global__ __launch_bounds__(GATE_TB) void gate_topk(const float* __restrict__ l
       float val = 0.f;
 #pragma unroll
       for (int u = 0; u < PG; ++u)
-        if (u == pass % PG) val = vv[u][i];
+        if (u == pi % PG) val = vv[u][i];
       v[i] = val;
       if (!(live && e < E)) taken |= 1u << i;
     }
@@ -300,7 +304,7 @@ __global__ __launch_bounds__(GATE_TB) void gate_topk(const float* __restrict__ l
   }
   __syncthreads();
   // stored [choice][expert][block] so the scan reads one (choice, expert) row contiguously
-  for (int i = tid; i < k * E; i += GATE_TB) blockhist[(int64_t)i * gridDim.x + blockIdx.x] = hist[i];
+  for (int i = threadIdx.x; i < k * E; i += GATE_TB * NWV) blockhist[(int64_t)i * gridDim.x + blockIdx.x] = hist[i];
 }
 
 // blockhist[j][e][b] -> blockbase[j][e][b] = queue position of the first (token, choice j) of
@@ -375,7 +379,8 @@ __global__ __launch_bounds__(GATE_TB) void gate_slots(const int32_t* __restrict_
 template <int W, int EPL>
 void launch_topk(const float* logits, int64_t S, int E, int k, int norm, int32_t* idx, float* w, int32_t* bh,
                  int nblk, hipStream_t st) {
-  hipLaunchKernelGGL((gate_topk<W, EPL>), dim3(nblk), dim3(GATE_TB), 0, st, logits, S, E, k, norm, idx, w, bh);
+  hipLaunchKernelGGL((gate_topk<W, EPL>), dim3(nblk), dim3(GATE_TB * (W < 8 ? W : 8)), 0, st, logits, S, E, k, norm,
+                     idx, w, bh);
 }
 
 }  // namespace
