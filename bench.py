@@ -91,6 +91,7 @@ def main():
         for t in (L.Xrecv, L.dYrecv):
             t.copy_(torch.randn(t.shape, generator=gen, device=dev, dtype=torch.float32).to(tdt))
             t[:, :, int(0.8 * L.C):, :] = 0
+        L.row_counts = torch.full((L.n_src, L.G), int(0.8 * L.C), dtype=torch.int32, device=dev)
         for t in (L.Yret, L.dbuf):
             t.copy_((torch.randn(t.shape, generator=gen, device=dev, dtype=torch.float32) * 0.5).to(tdt))
 
@@ -122,14 +123,21 @@ def main():
 
     # dominant kernel family: the six grouped GEMM launches of the expert FFN (2 fwd, 4 bwd),
     # each 2 * rows * M * H_l flops over the capacity-padded rows of the rank
+    # FLOPs = what the six launches multiply out: row tiles that are all capacity padding are skipped by the
+    # kernels and not counted (moe_ffn_executed_flops mirrors the kernels' skipping rule on a host copy of the counts)
     rows = L.n_src * L.G * L.C
-    flops_per_launch = 2.0 * rows * cfg.M * L.Hl
+    cnt_host = None if L.row_counts is None else L.row_counts.cpu().numpy()
+    dtc = api.MOE_BF16 if cfg.dtype == "bf16" else api.MOE_F32
+    executed = sum(api.moe_ffn_executed_flops(dtc, L.n_src, L.G, L.C, cfg.M, cfg.H, L.n_esp, cnt_host, b) for b in (0, 1))
+    flops_per_launch = executed / 6.0
+    occupied = rows if cnt_host is None else int(np.minimum(cnt_host, L.C).sum())
     gemm_ms = (per_call["ffn_fwd"] + per_call["ffn_bwd"]) / 6.0
     achieved = flops_per_launch / (gemm_ms * 1e-3) / 1e12
     roofline = {"bound": "mfma", "achieved": round(achieved, 2), "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
                 "frac": round(achieved / MFMA_BF16_PEAK_TFLOPS, 4), "traffic": MEASURED_TRAFFIC.get(cfg.name),
                 "kernel": "ffn_gemm_dma (6 launches per step)", "launch_ms": round(gemm_ms, 4),
-                "flops_per_launch": flops_per_launch}
+                "flops_per_launch": flops_per_launch, "occupied_rows": occupied, "capacity_rows": rows,
+                "flops_if_all_capacity_rows": 2.0 * rows * cfg.M * L.Hl}
     if cfg.dtype == "f32":
         roofline.update({"bound": "alu", "peak": 78.6, "frac": round(achieved / 78.6, 5),
                          "kernel": "ffn_gemm_f32 (6 launches per step)"})

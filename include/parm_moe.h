@@ -123,6 +123,14 @@ int moe_dispatch(const void* x, int dtype, int64_t S, int M, int E, int k, int64
  * (absolute error below 5e-5 resp. 2e-4, under the bf16 rounding of the stored result); fp32
  * uses erff.
  *
+ *   row_counts [n_src, G] int32, device, or NULL: the caller's promise that in chunk (s, g) the
+ *                        rows c >= min(row_counts[s,g], C) of X (and of dY in backward) are zero,
+ *                        i.e. capacity padding (counts from moe_gate_topk qualify when all experts
+ *                        are local).  Results are the same as without it -- FFN(0) = 0 and zero rows
+ *                        add nothing to the weight gradients -- but row tiles that hold nothing
+ *                        else are not multiplied (their outputs are stored as zeros), and with
+ *                        n_src = 1 the weight-gradient reductions stop at the count.
+ *
  * Backward (chain rule of the above), given dY [n_src,G,C,M] and the saved Z and A:
  *   dX  [n_src, G, C, M]  out
  *   dW1 [G, M, H], dW2 [G, H, M]  FULL tensors; only the shard's columns / rows are written
@@ -140,13 +148,23 @@ size_t moe_ffn_workspace_bytes(int dtype, int n_src, int G, int64_t C, int M, in
  * summation order.  Returns MOE_EINVAL for other values. */
 int moe_ffn_set_tile(int tile);
 
+/* Floating-point operations the forward (backward = 0: 2 GEMMs) or backward (backward = 1: 4 GEMMs)
+ * call multiplies out for this shape under the current tile setting: 2 * M * H_l per multiplied row
+ * and GEMM, where a row counts if it lies in a row tile that is not skipped (row-tiled GEMMs) or
+ * below the count (weight-gradient reductions, n_src = 1).  row_counts_host is a HOST copy of the
+ * row_counts passed to the calls, or NULL (every row is multiplied).  Pure host arithmetic, used by
+ * the benchmark to price the matrix pipes by executed work.  0 for invalid shapes. */
+double moe_ffn_executed_flops(int dtype, int n_src, int G, int64_t C, int M, int H, int n_esp,
+                              const int32_t* row_counts_host, int backward);
+
 int moe_expert_ffn_fwd(const void* X, int dtype, const void* W1, const void* W2,
                        int n_src, int G, int64_t C, int M, int H, int esp_idx, int n_esp,
-                       void* Z, void* A, void* Y, void* stream);
+                       const int32_t* row_counts, void* Z, void* A, void* Y, void* stream);
 
 int moe_expert_ffn_bwd(const void* dY, const void* X, const void* Z, const void* A,
                        const void* W1, const void* W2, int dtype,
                        int n_src, int G, int64_t C, int M, int H, int esp_idx, int n_esp,
+                       const int32_t* row_counts,
                        void* dX, void* dW1, void* dW2, void* ws, size_t ws_bytes, void* stream);
 
 /* ---------------------------------------------------------------------------------------

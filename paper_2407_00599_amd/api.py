@@ -50,14 +50,16 @@ def lib() -> ctypes.CDLL:
         L.moe_dispatch.argtypes = [c_p, c_i, c_i64, c_i, c_i, c_i, c_i64, c_p, c_p, c_p, c_p]
         L.moe_ffn_workspace_bytes.restype = c_sz
         L.moe_ffn_workspace_bytes.argtypes = [c_i, c_i, c_i, c_i64, c_i, c_i, c_i]
+        L.moe_ffn_executed_flops.restype = ctypes.c_double
+        L.moe_ffn_executed_flops.argtypes = [c_i, c_i, c_i, c_i64, c_i, c_i, c_i, c_p, c_i]
         L.moe_ffn_set_tile.restype = c_i
         L.moe_ffn_set_tile.argtypes = [c_i]
         L.moe_expert_ffn_fwd.restype = c_i
         L.moe_expert_ffn_fwd.argtypes = [c_p, c_i, c_p, c_p, c_i, c_i, c_i64, c_i, c_i, c_i, c_i,
-                                         c_p, c_p, c_p, c_p]
+                                         c_p, c_p, c_p, c_p, c_p]
         L.moe_expert_ffn_bwd.restype = c_i
         L.moe_expert_ffn_bwd.argtypes = [c_p, c_p, c_p, c_p, c_p, c_p, c_i, c_i, c_i, c_i64, c_i, c_i, c_i, c_i,
-                                         c_p, c_p, c_p, c_p, c_sz, c_p]
+                                         c_p, c_p, c_p, c_p, c_p, c_sz, c_p]
         L.moe_combine_fwd.restype = c_i
         L.moe_combine_fwd.argtypes = [c_p, c_i, c_i, c_i64, c_i, c_i, c_i, c_i64, c_p, c_p, c_p, c_p, c_p]
         L.moe_combine_bwd.restype = c_i
@@ -74,7 +76,7 @@ def lib() -> ctypes.CDLL:
 
 EXPORTED = [
     "moe_strerror", "moe_abi_version", "moe_capacity", "moe_gate_workspace_bytes", "moe_gate_topk",
-    "moe_dispatch", "moe_ffn_workspace_bytes", "moe_ffn_set_tile", "moe_expert_ffn_fwd", "moe_expert_ffn_bwd",
+    "moe_dispatch", "moe_ffn_workspace_bytes", "moe_ffn_set_tile", "moe_ffn_executed_flops", "moe_expert_ffn_fwd", "moe_expert_ffn_bwd",
     "moe_combine_fwd", "moe_combine_bwd", "moe_gate_bwd_workspace_bytes", "moe_gate_bwd",
 ]
 
@@ -149,15 +151,26 @@ def moe_dispatch(x, S, M, E, k, C, inv, w, buf):
            "moe_dispatch")
 
 
-def moe_expert_ffn_fwd(X, W1, W2, n_src, G, C, M, H, esp_idx, n_esp, Z, A, Y):
+def moe_ffn_executed_flops(dtype, n_src, G, C, M, H, n_esp, row_counts_host=None, backward=False) -> float:
+    """row_counts_host: a host int32 array [n_src, G] (numpy or CPU tensor) or None."""
+    ptr = None
+    if row_counts_host is not None:
+        import numpy as np
+        arr = np.ascontiguousarray(np.asarray(row_counts_host, dtype=np.int32))
+        assert arr.size == n_src * G
+        ptr = arr.ctypes.data_as(ctypes.c_void_p)
+    return float(lib().moe_ffn_executed_flops(dtype, n_src, G, C, M, H, n_esp, ptr, int(backward)))
+
+
+def moe_expert_ffn_fwd(X, W1, W2, n_src, G, C, M, H, esp_idx, n_esp, Z, A, Y, row_counts=None):
     _check(lib().moe_expert_ffn_fwd(_ptr(X), dtype_code(X), _ptr(W1), _ptr(W2), n_src, G, C, M, H, esp_idx, n_esp,
-                                    _ptr(Z), _ptr(A), _ptr(Y), _stream()), "moe_expert_ffn_fwd")
+                                    _ptr(row_counts), _ptr(Z), _ptr(A), _ptr(Y), _stream()), "moe_expert_ffn_fwd")
 
 
-def moe_expert_ffn_bwd(dY, X, Z, A, W1, W2, n_src, G, C, M, H, esp_idx, n_esp, dX, dW1, dW2, ws):
+def moe_expert_ffn_bwd(dY, X, Z, A, W1, W2, n_src, G, C, M, H, esp_idx, n_esp, dX, dW1, dW2, ws, row_counts=None):
     wp, wb = _ws_args(ws)
     _check(lib().moe_expert_ffn_bwd(_ptr(dY), _ptr(X), _ptr(Z), _ptr(A), _ptr(W1), _ptr(W2), dtype_code(X),
-                                    n_src, G, C, M, H, esp_idx, n_esp, _ptr(dX), _ptr(dW1), _ptr(dW2),
+                                    n_src, G, C, M, H, esp_idx, n_esp, _ptr(row_counts), _ptr(dX), _ptr(dW1), _ptr(dW2),
                                     wp, wb, _stream()), "moe_expert_ffn_bwd")
 
 

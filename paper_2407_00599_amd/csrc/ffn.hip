@@ -44,6 +44,7 @@ struct GemmArgs {
   void* C;
   void* C2;         // second output (the activation GeLU(Z)) for EPI_GELU
   const void* Zin;  // saved pre-activation for EPI_DGELU
+  const int32_t* cnt;  // optional [n_src, G]: rows of chunk (s, g) at or beyond min(cnt, Cc) are zero padding
   int G, n_src;
   int Cc;           // rows per chunk (capacity C)
   int R;            // n_src * Cc: virtual rows per expert
@@ -525,7 +526,7 @@ __device__ __forceinline__ void stb16(__amdgpu_buffer_rsrc_t r, uint32_t byte_of
 }
 template <int KIND, int EPI, int MB, int NBK>
 __device__ __forceinline__ void store_tile_lds(const GemmArgs& p, f32x16_t (&acc)[MB][NBK], char* wave_lds, int g,
-                                               int mbase, int nbase, int lane) {
+                                               int mbase, int nbase, int lane, bool zero_fill = false) {
   constexpr int CW = 32 * NBK;            // columns of the wave tile
   constexpr int PITCH_B = 2 * CW + 16;    // staged row pitch, bytes
   constexpr int BUF = 32 * PITCH_B;
@@ -589,6 +590,17 @@ __device__ __forceinline__ void store_tile_lds(const GemmArgs& p, f32x16_t (&acc
           off[i][t] = (m < p.Mdim && col_ok) ? (row * (uint32_t)p.ldc + (uint32_t)ncol) * 2u : OOB;
         }
     }
+  }
+  if (zero_fill) {   // a tile of padding rows: every result is zero
+    const uint4 z = make_uint4(0, 0, 0, 0);
+#pragma unroll
+    for (int i = 0; i < MB; ++i)
+#pragma unroll
+      for (int t = 0; t < NT_; ++t) {
+        stb16(rC, off[i][t], z);
+        if (EPI == EPI_GELU) stb16(rC2, off[i][t], z);
+      }
+    return;
   }
   // accumulator phase: row lane % 32, for block j and q4: 4 columns at 32 j + 8 q4 + 4 (lane / 32)
   const int acc_off = (lane & 31) * PITCH_B + (lane >> 5) * 8;
@@ -718,8 +730,13 @@ __global__ __launch_bounds__(128 * WN) void ffn_gemm_dma(const GemmArgs p) {
       (KIND == KIND_TN) ? make_rsrc(p.B, (uint32_t)p.b_bytes)
                         : make_rsrc(reinterpret_cast<const bf16_t*>(p.B) + b_base, b_rem > OOB ? OOB : (uint32_t)b_rem);
 
-  const int kpc = (p.Cc + DK - 1) / DK;  // TN: k tiles per chunk
-  const int nk = (KIND == KIND_TN) ? p.n_src * kpc : (p.Kdim + DK - 1) / DK;
+  // Rows at or beyond a chunk's count are padding (zero inputs, zero results).  A row tile made of
+  // nothing else stores zeros and leaves; a reduction over the rows (the weight gradients) stops at
+  // the count when there is a single chunk.
+  int kvalid = p.Cc;   // TN: rows of a chunk that are multiplied
+  if (KIND == KIND_TN && p.cnt != nullptr && p.n_src == 1) kvalid = min(max(p.cnt[g], 0), p.Cc);
+  const int kpc = max((kvalid + DK - 1) / DK, 1);  // TN: k tiles per chunk
+  const int nk = (KIND == KIND_TN) ? (kvalid > 0 ? p.n_src * kpc : 0) : (p.Kdim + DK - 1) / DK;
 
   // ---- per-lane request coordinates: each wave issues RPW requests per operand per k tile ----
   // k-contiguous operand, request q = RPW wave + j: rows 16 q + lane/4, slot lane%4 holds logical chunk kc_c
@@ -766,7 +783,7 @@ __global__ __launch_bounds__(128 * WN) void ffn_gemm_dma(const GemmArgs p) {
       const int c0 = (kt - s * kpc) * DK;
       const int64_t row0 = ((int64_t)s * p.G + g) * p.Cc + c0;
       add = (uint32_t)(row0 * (which ? p.ldb : p.lda) * 2);
-      lim = live ? p.Cc - c0 : 0;
+      lim = live ? kvalid - c0 : 0;
     } else {
       add = (which && B_NC) ? (uint32_t)((int64_t)kt * DK * p.ldb * 2) : (uint32_t)kt * (DK * 2);
       lim = live ? p.Kdim - kt * DK : 0;
@@ -879,6 +896,22 @@ __global__ __launch_bounds__(128 * WN) void ffn_gemm_dma(const GemmArgs p) {
   request_half(1, 0); request_half(1, 1);
   request_half(2, 0); request_half(2, 1);
   request_half(3, 0);
+  // The padding test comes after the first requests are on their way, so that reading the counts
+  // delays no tile that has work (a padding tile has fetched a few zeros for nothing).
+  if (KIND != KIND_TN && p.cnt != nullptr) {
+    const int r_end = min(m0 + TMR, p.Mdim);
+    bool pad = true;
+    for (int sc = m0 / p.Cc; sc * p.Cc < r_end; ++sc) {
+      const int c_lo = max(m0 - sc * p.Cc, 0);
+      if (c_lo < p.cnt[sc * p.G + g]) { pad = false; break; }
+    }
+    if (pad) {
+      __builtin_amdgcn_s_waitcnt(0x0070);   // the requests in flight write LDS: let them land before leaving
+      f32x16_t none[MB][NBK] = {};
+      store_tile_lds<KIND, EPI, MB, NBK>(p, none, smem, g, m0 + wm * (32 * MB), n0 + wn * (32 * NBK), lane, true);
+      return;
+    }
+  }
   // this wave's requests for tile 0 have landed (the 5 RPW issued after them may be in flight)
   __builtin_amdgcn_s_waitcnt(vmcnt_imm(5 * RPW));
   __builtin_amdgcn_s_barrier();
@@ -1044,6 +1077,32 @@ int num_cus() {
   return n;
 }
 
+// Which bf16 kernel and tile a grouped GEMM gets: tile_m x tile_n output tiles; dma = the LDS-DMA
+// kernel (the only one that skips padding rows).
+struct TilePlan {
+  bool big, dma;
+  int tile_m, tile_n;
+};
+TilePlan plan_tiles(bool tn, int G, int Mdim, int Ndim) {
+  TilePlan t;
+  const int64_t big_tiles = (int64_t)G * ((Mdim + 255) / 256) * ((Ndim + 255) / 256);
+  t.big = big_tiles >= 64;
+  if (g_tile_pref == 1) t.big = false;
+  if (g_tile_pref >= 2) t.big = true;
+  t.tile_n = t.big ? 256 : 128;
+  t.tile_m = t.tile_n;
+  t.dma = t.big && (g_tile_pref == 0 || g_tile_pref == 2 || g_tile_pref == 6 || g_tile_pref == 7);
+  // 192-row tiles when they need no more rounds of the chip's compute units (weighted by tile height)
+  if (t.big && !tn && (g_tile_pref == 0 || g_tile_pref == 7)) {
+    const int64_t tiles_n = (Ndim + 255) / 256;
+    const int64_t t256 = (int64_t)G * ((Mdim + 255) / 256) * tiles_n;
+    const int64_t t192 = (int64_t)G * ((Mdim + 191) / 192) * tiles_n;
+    const int64_t cu = num_cus();
+    if (g_tile_pref == 7 || ((t192 + cu - 1) / cu) * 192 <= ((t256 + cu - 1) / cu) * 256) t.tile_m = 192;
+  }
+  return t;
+}
+
 template <int KIND, int EPI>
 void launch_gemm(GemmArgs a, int dtype, hipStream_t st) {
   if (dtype == MOE_F32) {
@@ -1057,33 +1116,20 @@ void launch_gemm(GemmArgs a, int dtype, hipStream_t st) {
   const uint64_t act_rows = (uint64_t)a.n_src * a.G * a.Cc;
   a.a_bytes = act_rows * (uint64_t)a.lda * 2;
   a.b_bytes = (KIND == KIND_TN) ? act_rows * (uint64_t)a.ldb * 2 : (uint64_t)a.G * (uint64_t)a.b_goff * 2;
-  const int64_t big_tiles = (int64_t)a.G * ((a.Mdim + 255) / 256) * ((a.Ndim + 255) / 256);
-  bool big = big_tiles >= 64;
-  if (g_tile_pref == 1) big = false;
-  if (g_tile_pref >= 2) big = true;
-  const int T = big ? 256 : 128;
-  a.tiles_n = (a.Ndim + T - 1) / T;
-  // 192-row tiles when they need fewer rounds of the chip's compute units (weighted by tile height)
-  bool low = false;
-  if (big && KIND != KIND_TN && (g_tile_pref == 0 || g_tile_pref == 7)) {
-    const int64_t t256 = (int64_t)a.G * ((a.Mdim + 255) / 256) * a.tiles_n;
-    const int64_t t192 = (int64_t)a.G * ((a.Mdim + 191) / 192) * a.tiles_n;
-    const int64_t cu = num_cus();
-    low = g_tile_pref == 7 || ((t192 + cu - 1) / cu) * 192 < ((t256 + cu - 1) / cu) * 256;
-  }
-  const int TMh = low ? 192 : T;
-  a.tiles_m = (a.Mdim + TMh - 1) / TMh;
+  const TilePlan t = plan_tiles(KIND == KIND_TN, a.G, a.Mdim, a.Ndim);
+  a.tiles_n = (a.Ndim + t.tile_n - 1) / t.tile_n;
+  a.tiles_m = (a.Mdim + t.tile_m - 1) / t.tile_m;
   a.total_tiles = a.G * a.tiles_m * a.tiles_n;
   const dim3 grid((unsigned)(((a.total_tiles + 7) / 8) * 8));
-  if (low) {
+  if (t.tile_m == 192) {
     if constexpr (KIND != KIND_TN) hipLaunchKernelGGL((ffn_gemm_dma<KIND, EPI, 4, 192>), grid, dim3(512), 0, st, a);
-  } else if (big && (g_tile_pref == 0 || g_tile_pref == 6 || g_tile_pref == 7))
+  } else if (t.dma && g_tile_pref != 2)
     hipLaunchKernelGGL((ffn_gemm_dma<KIND, EPI, 4>), grid, dim3(512), 0, st, a);
-  else if (big && g_tile_pref == 2)
+  else if (t.dma)
     hipLaunchKernelGGL((ffn_gemm_dma<KIND, EPI, 2>), grid, dim3(256), 0, st, a);
-  else if (big && g_tile_pref == 3) hipLaunchKernelGGL((ffn_gemm_bf16<256, 256, 2, 4, KIND, EPI>), grid, dim3(512), 0, st, a);
-  else if (big && g_tile_pref == 4) hipLaunchKernelGGL((ffn_gemm_bf16<256, 256, 4, 2, KIND, EPI>), grid, dim3(512), 0, st, a);
-  else if (big) hipLaunchKernelGGL((ffn_gemm_bf16<256, 256, 2, 2, KIND, EPI>), grid, dim3(256), 0, st, a);
+  else if (t.big && g_tile_pref == 3) hipLaunchKernelGGL((ffn_gemm_bf16<256, 256, 2, 4, KIND, EPI>), grid, dim3(512), 0, st, a);
+  else if (t.big && g_tile_pref == 4) hipLaunchKernelGGL((ffn_gemm_bf16<256, 256, 4, 2, KIND, EPI>), grid, dim3(512), 0, st, a);
+  else if (t.big) hipLaunchKernelGGL((ffn_gemm_bf16<256, 256, 2, 2, KIND, EPI>), grid, dim3(256), 0, st, a);
   else hipLaunchKernelGGL((ffn_gemm_bf16<128, 128, 2, 2, KIND, EPI>), grid, dim3(256), 0, st, a);
 }
 
@@ -1110,6 +1156,48 @@ extern "C" int moe_ffn_set_tile(int tile) {
   return MOE_OK;
 }
 
+// multiplied rows of a row-tiled GEMM (outputs [R rows per expert] x N), or of the reduction of a
+// weight-gradient GEMM, given host-side row counts
+static double rows_multiplied(bool tn, int dtype, int n_src, int G, int64_t C, int Mdim, int Ndim,
+                              const int32_t* cnt) {
+  const int64_t R = (int64_t)n_src * C;
+  const TilePlan t = plan_tiles(tn, G, Mdim, Ndim);
+  if (cnt == nullptr || dtype != MOE_BF16 || !t.dma) return (double)G * (double)R;
+  double rows = 0;
+  for (int g = 0; g < G; ++g) {
+    if (tn) {
+      if (n_src != 1) { rows += (double)R; continue; }
+      const int64_t c = cnt[g] < 0 ? 0 : cnt[g];
+      rows += (double)(c < C ? c : C);
+    } else {
+      for (int64_t m0 = 0; m0 < R; m0 += t.tile_m) {
+        const int64_t r_end = m0 + t.tile_m < R ? m0 + t.tile_m : R;
+        bool pad = true;
+        for (int64_t sc = m0 / C; sc * C < r_end; ++sc) {
+          const int64_t c_lo = m0 - sc * C > 0 ? m0 - sc * C : 0;
+          if (c_lo < cnt[sc * G + g]) { pad = false; break; }
+        }
+        if (!pad) rows += (double)(r_end - m0);
+      }
+    }
+  }
+  return rows;
+}
+
+extern "C" double moe_ffn_executed_flops(int dtype, int n_src, int G, int64_t C, int M, int H, int n_esp,
+                                         const int32_t* row_counts_host, int backward) {
+  if (check_ffn_shape(dtype, n_src, G, C, M, H, 0, n_esp) != MOE_OK) return 0.0;
+  const int Hl = H / n_esp;
+  const int R = (int)(n_src * C);
+  const int32_t* c = row_counts_host;
+  const double mh = 2.0 * (double)M * (double)Hl;
+  if (!backward)   // Z = X W1 (rows x Hl), Y = A W2 (rows x M)
+    return mh * (rows_multiplied(false, dtype, n_src, G, C, R, Hl, c) + rows_multiplied(false, dtype, n_src, G, C, R, M, c));
+  // dA = dY W2^T (rows x Hl), dW2 (Hl x M over the rows), dW1 (M x Hl over the rows), dX = dZ W1^T (rows x M)
+  return mh * (rows_multiplied(false, dtype, n_src, G, C, R, Hl, c) + rows_multiplied(true, dtype, n_src, G, C, Hl, M, c) +
+               rows_multiplied(true, dtype, n_src, G, C, M, Hl, c) + rows_multiplied(false, dtype, n_src, G, C, R, M, c));
+}
+
 extern "C" size_t moe_ffn_workspace_bytes(int dtype, int n_src, int G, int64_t C, int M, int H, int n_esp) {
   if (check_ffn_shape(dtype, n_src, G, C, M, H, 0, n_esp) != MOE_OK) return 0;
   const size_t esz = dtype == MOE_BF16 ? 2 : 4;
@@ -1117,17 +1205,18 @@ extern "C" size_t moe_ffn_workspace_bytes(int dtype, int n_src, int G, int64_t C
 }
 
 extern "C" int moe_expert_ffn_fwd(const void* X, int dtype, const void* W1, const void* W2, int n_src, int G,
-                                  int64_t C, int M, int H, int esp_idx, int n_esp, void* Z, void* A, void* Y,
-                                  void* stream) {
+                                  int64_t C, int M, int H, int esp_idx, int n_esp, const int32_t* row_counts, void* Z,
+                                  void* A, void* Y, void* stream) {
   if (int rc = check_ffn_shape(dtype, n_src, G, C, M, H, esp_idx, n_esp)) return rc;
   MOE_REQUIRE_PTR(X); MOE_REQUIRE_PTR(W1); MOE_REQUIRE_PTR(W2); MOE_REQUIRE_PTR(Z); MOE_REQUIRE_PTR(A);
   MOE_REQUIRE_PTR(Y);
+  MOE_REQUIRE((((uintptr_t)row_counts) & 3u) == 0, MOE_EALIGN);
   hipStream_t st = (hipStream_t)stream;
   const int Hl = H / n_esp;
   const int64_t h0 = (int64_t)esp_idx * Hl;
 
   GemmArgs a{};
-  a.G = G; a.n_src = n_src; a.Cc = (int)C; a.R = (int)(n_src * C);
+  a.G = G; a.n_src = n_src; a.Cc = (int)C; a.R = (int)(n_src * C); a.cnt = row_counts;
   // Z = X * W1[:, h0:h0+Hl] ; A = GeLU(Z)
   a.A = X; a.lda = M;
   a.B = W1; a.ldb = H; a.b_goff = (int64_t)M * H; a.b_off = h0;
@@ -1145,13 +1234,15 @@ extern "C" int moe_expert_ffn_fwd(const void* X, int dtype, const void* W1, cons
 
 extern "C" int moe_expert_ffn_bwd(const void* dY, const void* X, const void* Z, const void* A, const void* W1,
                                   const void* W2, int dtype, int n_src, int G, int64_t C, int M, int H, int esp_idx,
-                                  int n_esp, void* dX, void* dW1, void* dW2, void* ws, size_t ws_bytes, void* stream) {
+                                  int n_esp, const int32_t* row_counts, void* dX, void* dW1, void* dW2, void* ws,
+                                  size_t ws_bytes, void* stream) {
   if (int rc = check_ffn_shape(dtype, n_src, G, C, M, H, esp_idx, n_esp)) return rc;
   MOE_REQUIRE_PTR(dY); MOE_REQUIRE_PTR(X); MOE_REQUIRE_PTR(Z); MOE_REQUIRE_PTR(A); MOE_REQUIRE_PTR(W1);
   MOE_REQUIRE_PTR(W2); MOE_REQUIRE_PTR(dX); MOE_REQUIRE_PTR(dW1); MOE_REQUIRE_PTR(dW2);
   const size_t need = moe_ffn_workspace_bytes(dtype, n_src, G, C, M, H, n_esp);
   MOE_REQUIRE(ws != nullptr && ws_bytes >= need, MOE_EWORKSPACE);
   MOE_REQUIRE(moe::aligned16(ws), MOE_EALIGN);
+  MOE_REQUIRE((((uintptr_t)row_counts) & 3u) == 0, MOE_EALIGN);
   hipStream_t st = (hipStream_t)stream;
   const int Hl = H / n_esp;
   const int64_t h0 = (int64_t)esp_idx * Hl;
@@ -1159,7 +1250,7 @@ extern "C" int moe_expert_ffn_bwd(const void* dY, const void* X, const void* Z, 
   void* dZ = ws;
 
   GemmArgs a{};
-  a.G = G; a.n_src = n_src; a.Cc = (int)C; a.R = (int)(n_src * C);
+  a.G = G; a.n_src = n_src; a.Cc = (int)C; a.R = (int)(n_src * C); a.cnt = row_counts;
   // dA = dY * W2[h0:h0+Hl, :]^T ; dZ = dA * GeLU'(Z)
   a.A = dY; a.lda = M;
   a.B = W2; a.ldb = M; a.b_goff = (int64_t)H * M; a.b_off = h0 * M;

@@ -55,7 +55,8 @@ class MoERankLayer:
         self.gate(x_full, Wg, bias)
         api.moe_dispatch(self.x, S, M, E, k, C, self.inv, None, self.buf)
         for j in range(self.n_esp):           # the N_ESP shards of every expert, one after the other
-            api.moe_expert_ffn_fwd(self.buf, W1, W2, 1, E, C, M, H, j, self.n_esp, self.Z[j], self.A[j], self.Yret[j])
+            api.moe_expert_ffn_fwd(self.buf, W1, W2, 1, E, C, M, H, j, self.n_esp, self.Z[j], self.A[j], self.Yret[j],
+                                   self.counts)
         api.moe_combine_fwd(self.Yret, self.n_esp, S, M, E, k, C, self.idx, self.slot, self.w, self.y)
         return self.y
 
@@ -65,8 +66,7 @@ class MoERankLayer:
                             self.dYret, self.dw)
         for j in range(self.n_esp):
             api.moe_expert_ffn_bwd(self.dYret, self.buf, self.Z[j], self.A[j], self.W1, self.W2, 1, E, C, M, H, j,
-                                   self.n_esp,
-                                   self.dbuf[j], self.dW1, self.dW2, self.ws)
+                                   self.n_esp, self.dbuf[j], self.dW1, self.dW2, self.ws, self.counts)
         # backward of dispatch = unweighted combine of the (n_esp partial) input gradients
         api.moe_combine_fwd(self.dbuf, self.n_esp, S, M, E, k, C, self.idx, self.slot, None, self.dx)
         api.moe_gate_bwd(self.dw, self.w, self.idx, self.logits, self.x, self.Wg, S, M, E, k, self.norm_topk,
@@ -114,9 +114,11 @@ class MoERankShape:
         if self.closed:
             self.Xrecv, self.Yret, self.dYrecv, self.dbuf = self.buf.view(1, E, C, M), self.Yout, \
                 self.dYret.view(1, E, C, M), self.dXout
+            self.row_counts = self.counts      # every expert is local: the gate's demand counts name the padding
         else:
             self.Xrecv = e(n_src, G, C, M); self.Yret = e(n_esp, E, C, M)
             self.dYrecv = e(n_src, G, C, M); self.dbuf = e(n_esp, E, C, M)
+            self.row_counts = None             # [n_src, G] occupancy that would arrive with the AlltoAll; set by the caller
         nbytes = max(api.moe_gate_workspace_bytes(S, E, k),
                      api.moe_ffn_workspace_bytes(self.dt, n_src, G, C, M, H, n_esp),
                      api.moe_gate_bwd_workspace_bytes(S, M, E), 256)
@@ -138,7 +140,7 @@ class MoERankShape:
 
     def ffn_fwd(self):
         api.moe_expert_ffn_fwd(self.Xrecv, self.W1, self.W2, self.n_src, self.G, self.C, self.M, self.H, self.esp_idx,
-                               self.n_esp, self.Z, self.A, self.Yout)
+                               self.n_esp, self.Z, self.A, self.Yout, self.row_counts)
 
     def combine(self):
         api.moe_combine_fwd(self.Yret, self.n_esp, self.S, self.M, self.E, self.k, self.C, self.idx, self.slot,
@@ -149,8 +151,9 @@ class MoERankShape:
                             self.slot, self.inv, self.w, self.dYret, self.dw)
 
     def ffn_bwd(self):
-        api.moe_expert_ffn_bwd(self.dYrecv, self.Xrecv, self.Z, self.A, self.W1, self.W2, self.n_src, self.G, self.C, self.M,
-                               self.H, self.esp_idx, self.n_esp, self.dXout, self.dW1, self.dW2, self.ws)
+        api.moe_expert_ffn_bwd(self.dYrecv, self.Xrecv, self.Z, self.A, self.W1, self.W2, self.n_src, self.G, self.C,
+                               self.M, self.H, self.esp_idx, self.n_esp, self.dXout, self.dW1, self.dW2, self.ws,
+                               self.row_counts)
 
     def dispatch_bwd(self):
         api.moe_combine_fwd(self.dbuf, self.n_esp, self.S, self.M, self.E, self.k, self.C, self.idx, self.slot, None,

@@ -35,7 +35,7 @@ def test_every_declared_symbol_is_exported_and_bound(L):
     for n in names:                       # the Python binding has the same names
         if n not in ("moe_strerror", "moe_abi_version"):
             assert hasattr(api, n), n
-    assert L.moe_abi_version() == 2
+    assert L.moe_abi_version() == 3
 
 
 def test_error_strings(L):
@@ -109,7 +109,7 @@ def test_ffn_argument_checks(L):
     assert f(1, 2, 4, 100, 64, 250, 4) == 0                 # H % n_esp != 0 -> invalid -> 0
 
     def fwd(dt=1, n_src=1, G=2, C=10, M=64, H=128, e=0, n=1, X=A, Z=A, Act=A):
-        return L.moe_expert_ffn_fwd(X, dt, A, A, n_src, G, C, M, H, e, n, Z, Act, A, None)
+        return L.moe_expert_ffn_fwd(X, dt, A, A, n_src, G, C, M, H, e, n, None, Z, Act, A, None)
     assert fwd(H=130, n=4) == -1
     assert fwd(e=2, n=2) == -1
     assert fwd(e=-1) == -1
@@ -120,11 +120,42 @@ def test_ffn_argument_checks(L):
     assert fwd(X=None) == -6
     assert fwd(Z=U) == -3
     assert fwd(Act=None) == -6
-    assert L.moe_expert_ffn_bwd(A, A, A, A, A, A, 1, 1, 2, 10, 64, 128, 0, 1, A, A, None, A, 1 << 30, None) == -6
-    assert L.moe_expert_ffn_bwd(A, A, A, None, A, A, 1, 1, 2, 10, 64, 128, 0, 1, A, A, A, A, 1 << 30, None) == -6
-    assert L.moe_expert_ffn_bwd(A, A, A, A, A, A, 1, 1, 2, 10, 64, 128, 0, 1, A, A, A, A, 64, None) == -5
-    assert L.moe_expert_ffn_bwd(A, A, A, A, A, A, 1, 1, 2, 10, 64, 128, 0, 1, A, A, A, None, 1 << 30, None) == -5
+    assert L.moe_expert_ffn_bwd(A, A, A, A, A, A, 1, 1, 2, 10, 64, 128, 0, 1, None, A, A, None, A, 1 << 30, None) == -6
+    assert L.moe_expert_ffn_bwd(A, A, A, None, A, A, 1, 1, 2, 10, 64, 128, 0, 1, None, A, A, A, A, 1 << 30, None) == -6
+    assert L.moe_expert_ffn_bwd(A, A, A, A, A, A, 1, 1, 2, 10, 64, 128, 0, 1, None, A, A, A, A, 64, None) == -5
+    assert L.moe_expert_ffn_bwd(A, A, A, A, A, A, 1, 1, 2, 10, 64, 128, 0, 1, None, A, A, A, None, 1 << 30, None) == -5
     assert L.moe_ffn_set_tile(8) == -1 and L.moe_ffn_set_tile(-1) == -1 and L.moe_ffn_set_tile(0) == 0
+
+
+def test_executed_flops_accounting(L):
+    """Host arithmetic only: executed work of the FFN calls for given row counts."""
+    import numpy as np
+    f = api.moe_ffn_executed_flops
+    n_src, G, C, M, H = 1, 8, 1229, 1024, 4096
+    full = 2.0 * G * C * M * H
+    assert f(api.MOE_BF16, n_src, G, C, M, H, 1) == 2 * full                 # two GEMMs over every row
+    assert f(api.MOE_BF16, n_src, G, C, M, H, 1, None, True) == 4 * full
+    assert f(api.MOE_F32, n_src, G, C, M, H, 1, np.zeros((1, G), np.int32)) == 2 * full   # fp32 kernels never skip
+    assert f(api.MOE_BF16, n_src, G, C, M, H, 1, np.full((1, G), C, np.int32)) == 2 * full
+    assert f(api.MOE_BF16, n_src, G, C, M, 4100, 3) == 0.0                 # invalid shape
+    # empty experts: nothing is multiplied, forward or backward
+    assert f(api.MOE_BF16, n_src, G, C, M, H, 1, np.zeros((1, G), np.int32)) == 0.0
+    assert f(api.MOE_BF16, n_src, G, C, M, H, 1, np.zeros((1, G), np.int32), True) == 0.0
+    # one token per expert: one row tile per expert in the row-tiled GEMMs, one row in the reductions
+    one = np.ones((1, G), np.int32)
+    api.moe_ffn_set_tile(6)      # 256-row tiles everywhere
+    try:
+        assert f(api.MOE_BF16, n_src, G, C, M, H, 1, one) == 2 * (2.0 * G * 256 * M * H)
+        assert f(api.MOE_BF16, n_src, G, C, M, H, 1, one, True) == 2 * (2.0 * G * 256 * M * H) + 2 * (2.0 * G * 1 * M * H)
+        # counts above the capacity are clamped; a count on a tile edge needs no further tile
+        assert f(api.MOE_BF16, n_src, G, C, M, H, 1, np.full((1, G), C + 7, np.int32), True) == 4 * full
+        assert f(api.MOE_BF16, n_src, G, C, M, H, 1, np.full((1, G), 512, np.int32)) == 2 * (2.0 * G * 512 * M * H)
+        assert f(api.MOE_BF16, n_src, G, C, M, H, 1, np.full((1, G), 513, np.int32)) == 2 * (2.0 * G * 768 * M * H)
+        # several source chunks: the reductions run over all rows, the row tiles follow each chunk's count
+        got = f(api.MOE_BF16, 2, G, 1024, M, H, 1, np.array([[0] * G, [1] * G], np.int32), True)
+        assert got == 2 * (2.0 * G * 256 * M * H) + 2 * (2.0 * G * 2048 * M * H)
+    finally:
+        api.moe_ffn_set_tile(0)
 
 
 def test_gate_bwd_argument_checks(L):

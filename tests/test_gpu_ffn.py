@@ -14,7 +14,7 @@ from util import DEV, TOL, to_dev, to_host, rel_err, torch_dtype
 pytestmark = pytest.mark.gpu
 
 
-def gpu_ffn(X, dY, W1, W2, n_src, G, C, M, H, esp_idx, n_esp, tdt):
+def gpu_ffn(X, dY, W1, W2, n_src, G, C, M, H, esp_idx, n_esp, tdt, row_counts=None):
     Hl = H // n_esp
     dt = api.MOE_BF16 if tdt == torch.bfloat16 else api.MOE_F32
     Z = torch.empty(n_src, G, C, Hl, dtype=tdt, device=DEV); Y = torch.empty(n_src, G, C, M, dtype=tdt, device=DEV)
@@ -22,8 +22,8 @@ def gpu_ffn(X, dY, W1, W2, n_src, G, C, M, H, esp_idx, n_esp, tdt):
     dW1 = torch.full((G, M, H), 3.0, dtype=tdt, device=DEV); dW2 = torch.full((G, H, M), 3.0, dtype=tdt, device=DEV)
     A = torch.empty_like(Z)
     ws = torch.empty(api.moe_ffn_workspace_bytes(dt, n_src, G, C, M, H, n_esp), dtype=torch.uint8, device=DEV)
-    api.moe_expert_ffn_fwd(X, W1, W2, n_src, G, C, M, H, esp_idx, n_esp, Z, A, Y)
-    api.moe_expert_ffn_bwd(dY, X, Z, A, W1, W2, n_src, G, C, M, H, esp_idx, n_esp, dX, dW1, dW2, ws)
+    api.moe_expert_ffn_fwd(X, W1, W2, n_src, G, C, M, H, esp_idx, n_esp, Z, A, Y, row_counts)
+    api.moe_expert_ffn_bwd(dY, X, Z, A, W1, W2, n_src, G, C, M, H, esp_idx, n_esp, dX, dW1, dW2, ws, row_counts)
     torch.cuda.synchronize()
     return Z, A, Y, dX, dW1, dW2
 
@@ -85,6 +85,36 @@ def test_ffn_fwd_bwd_elementwise(n_src, G, C, M, H, n_esp, esp_idx, dtype, tile)
     # padding rows produce exact zeros
     zero_rows = ~X.val.any(axis=-1)
     assert np.all(to_host(Y)[zero_rows] == 0.0)
+
+
+@pytest.mark.parametrize("n_src,G,C,M,H,occ,tile", [
+    (1, 3, 700, 256, 512, [[0, 130, 700]], 0),          # an empty expert, one short, one full (auto tiles)
+    (1, 3, 700, 256, 512, [[1, 257, 900]], 6),          # a demand count above the capacity
+    (1, 2, 600, 264, 520, [[193, 384]], 7),             # 192-row tiles, counts at tile edges
+    (3, 2, 300, 256, 512, [[0, 300], [40, 0], [299, 1]], 0),   # several source chunks
+    (2, 1, 150, 128, 256, [[10, ], [149, ]], 1),        # small problem: the register-staged kernel ignores the counts
+])
+def test_row_counts_change_nothing(n_src, G, C, M, H, occ, tile):
+    """Telling the FFN which rows are capacity padding must not change any result (only the time)."""
+    rng = np.random.default_rng(99)
+    Xn = rng.standard_normal((n_src, G, C, M)).astype(np.float32)
+    dYn = rng.standard_normal((n_src, G, C, M)).astype(np.float32)
+    for s in range(n_src):
+        for g in range(G):
+            Xn[s, g, occ[s][g]:] = 0; dYn[s, g, occ[s][g]:] = 0
+    X, dY = to_dev(synth.store(Xn, "bf16")), to_dev(synth.store(dYn, "bf16"))
+    W1 = to_dev(synth.store((rng.standard_normal((G, M, H)) / np.sqrt(M)).astype(np.float32), "bf16"))
+    W2 = to_dev(synth.store((rng.standard_normal((G, H, M)) / np.sqrt(H)).astype(np.float32), "bf16"))
+    cnt = torch.tensor(occ, dtype=torch.int32, device=DEV)
+    api.moe_ffn_set_tile(tile)
+    try:
+        ref = gpu_ffn(X, dY, W1, W2, n_src, G, C, M, H, 0, 1, torch.bfloat16)
+        got = gpu_ffn(X, dY, W1, W2, n_src, G, C, M, H, 0, 1, torch.bfloat16, cnt)
+    finally:
+        api.moe_ffn_set_tile(0)
+    for name, a, b in zip(("Z", "A", "Y", "dX", "dW1", "dW2"), ref, got):
+        assert torch.equal(a.float(), b.float()), name      # == on values: -0 and +0 count as equal
+    assert not (ref[2][X.abs().sum(-1) == 0] != 0).any()
 
 
 def _device_inputs(cfg, C, seed):
