@@ -335,6 +335,43 @@ def layer_bwd(r, dy, x, Wg, W1, W2, k: int, norm_topk: bool, n_esp: int = 1):
 
 
 # --------------------------------------------------------------------------- #
+# Schedule S2 of Section III-B ("Dedicated Schedules"): MP is paused AFTER the gate and
+# resumed BEFORE the combine.  Gate and dispatch see all B*L tokens of the MP group (the
+# capacity comes from B*L); the MP-Split then leaves MP rank r one part of the dispatched
+# [E,C,M] buffer, the experts work on that part, and the MP-AllGather puts the parts back
+# together before the combine.  The paper does not say how the buffer is cut; here rank r
+# of n takes the contiguous slot range [floor(r C / n), floor((r+1) C / n)) of every expert.
+# --------------------------------------------------------------------------- #
+def slot_range(C: int, mp_idx: int, n_mp: int):
+    if not (n_mp >= 1 and 0 <= mp_idx < n_mp):
+        raise ValueError("bad MP rank")
+    return (mp_idx * C) // n_mp, ((mp_idx + 1) * C) // n_mp
+
+
+def layer_fwd_s2(x_full, Wg, bias, W1, W2, k: int, f: float, norm_topk: bool, n_mp: int, n_esp: int = 1):
+    """All n_mp ranks of one MP group, one after the other: returns the routing record (with the
+    per-rank buffers in r["buf_parts"]) and y for ALL tokens of the group."""
+    r = route(x_full, Wg, bias, k, f, norm_topk)
+    C = r["C"]
+    E = r["inv"].shape[0]
+    Yret = np.zeros((n_esp, E, C, W2.shape[2]), dtype=F64)
+    parts = []
+    for rank in range(n_mp):
+        c0, c1 = slot_range(C, rank, n_mp)
+        if c1 == c0:
+            parts.append(np.zeros((E, 0, x_full.shape[1]), dtype=F64))
+            continue
+        part = dispatch(x_full, r["inv"][:, c0:c1], k)           # MP-Split of the dispatched buffer
+        parts.append(part)
+        for j in range(n_esp):
+            _, Yj = expert_ffn_fwd(part[None], W1, W2, j, n_esp)
+            Yret[j, :, c0:c1] = Yj[0]                             # MP-AllGather: the parts side by side
+    y = combine_fwd(Yret, r["idx"], r["slot"], r["w"])
+    r.update(buf_parts=parts, Yret=Yret, y=y)
+    return r
+
+
+# --------------------------------------------------------------------------- #
 # The same expert FFN evaluated for single rows / single hidden units, so that
 # outputs of a full-size run can be checked one by one.
 # --------------------------------------------------------------------------- #
