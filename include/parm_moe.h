@@ -107,6 +107,20 @@ int moe_gate_topk(const void* x, int x_dtype, const float* Wg, const float* gate
 int moe_dispatch(const void* x, int dtype, int64_t S, int M, int E, int k, int64_t C,
                  const int32_t* inv, const float* w, void* buf, void* stream);
 
+/* Schedule S2 (Section III-B: MP is paused after the gate and resumed before the combine): the
+ * gate runs on all B*L tokens of the MP group (moe_gate_topk with n_mp = 1, so the capacity
+ * comes from B*L), and the MP-Split then hands each MP rank one part of the dispatched [E,C,M]
+ * buffer.  This call writes only the rank's part, the slots c0 <= c < c1 of every expert:
+ *   buf [E, c1-c0, M],  buf[e, c-c0, :] = x[t,:] (times w[t,j]) for (t,j) = inv[e,c], else 0.
+ * The part of rank r out of n is c0 = floor(r*C/n), c1 = floor((r+1)*C/n) (the paper fixes no
+ * particular split; contiguous slot ranges keep each part a dense [E,*,M] AlltoAll buffer).  The
+ * expert FFN then runs with C := c1-c0; after the MP-AllGather the parts form the full
+ * [E,C,M] buffer that moe_combine_fwd reads.  With w != NULL this is also the rank's part of
+ * the combine backward (dYret).  MOE_EINVAL unless 0 <= c0 < c1 <= C. */
+int moe_dispatch_slots(const void* x, int dtype, int64_t S, int M, int E, int k, int64_t C,
+                       int64_t c0, int64_t c1, const int32_t* inv, const float* w, void* buf,
+                       void* stream);
+
 /* ---------------------------------------------------------------------------------------
  * Expert FFN on one ESP shard: Section II-A "Experts" (weights (M,H) and (H,M) around an
  * activation) with the hidden dimension split as in Y = sum_p W2^(p) f(W1^(p) X) (Section
@@ -180,6 +194,8 @@ int moe_expert_ffn_bwd(const void* dY, const void* X, const void* Z, const void*
  * Backward:  dYret [E, C, M] = w[t,j] * dy[t,:] at the occupant's slot, zeros at empty slots
  *            (every partial sum receives this same gradient);
  *            dw[t,j] = < dy[t,:], sum_p Yret[p, idx[t,j], slot[t,j], :] >, 0 if dropped.
+ *            dYret may be NULL (only dw is wanted: under S2 the rank's slot range of dYret
+ *            comes from moe_dispatch_slots(dy, ..., w, ...)).
  * --------------------------------------------------------------------------------------- */
 int moe_combine_fwd(const void* Yret, int dtype, int n_part, int64_t S, int M, int E, int k,
                     int64_t C, const int32_t* idx, const int32_t* slot, const float* w,

@@ -50,6 +50,8 @@ def lib() -> ctypes.CDLL:
         L.moe_dispatch.argtypes = [c_p, c_i, c_i64, c_i, c_i, c_i, c_i64, c_p, c_p, c_p, c_p]
         L.moe_ffn_workspace_bytes.restype = c_sz
         L.moe_ffn_workspace_bytes.argtypes = [c_i, c_i, c_i, c_i64, c_i, c_i, c_i]
+        L.moe_dispatch_slots.restype = c_i
+        L.moe_dispatch_slots.argtypes = [c_p, c_i, c_i64, c_i, c_i, c_i, c_i64, c_i64, c_i64, c_p, c_p, c_p, c_p]
         L.moe_ffn_executed_flops.restype = ctypes.c_double
         L.moe_ffn_executed_flops.argtypes = [c_i, c_i, c_i, c_i64, c_i, c_i, c_i, c_p, c_i]
         L.moe_ffn_set_tile.restype = c_i
@@ -76,7 +78,7 @@ def lib() -> ctypes.CDLL:
 
 EXPORTED = [
     "moe_strerror", "moe_abi_version", "moe_capacity", "moe_gate_workspace_bytes", "moe_gate_topk",
-    "moe_dispatch", "moe_ffn_workspace_bytes", "moe_ffn_set_tile", "moe_ffn_executed_flops", "moe_expert_ffn_fwd", "moe_expert_ffn_bwd",
+    "moe_dispatch", "moe_dispatch_slots", "moe_ffn_workspace_bytes", "moe_ffn_set_tile", "moe_ffn_executed_flops", "moe_expert_ffn_fwd", "moe_expert_ffn_bwd",
     "moe_combine_fwd", "moe_combine_bwd", "moe_gate_bwd_workspace_bytes", "moe_gate_bwd",
 ]
 
@@ -149,6 +151,11 @@ def moe_gate_topk(x, Wg, gate_bias, S_total, M, E, k, C, mp_idx, n_mp, norm_topk
 def moe_dispatch(x, S, M, E, k, C, inv, w, buf):
     _check(lib().moe_dispatch(_ptr(x), dtype_code(x), S, M, E, k, C, _ptr(inv), _ptr(w), _ptr(buf), _stream()),
            "moe_dispatch")
+
+
+def moe_dispatch_slots(x, S, M, E, k, C, c0, c1, inv, w, buf):
+    _check(lib().moe_dispatch_slots(_ptr(x), dtype_code(x), S, M, E, k, C, c0, c1, _ptr(inv), _ptr(w), _ptr(buf),
+                                    _stream()), "moe_dispatch_slots")
 
 
 def moe_ffn_executed_flops(dtype, n_src, G, C, M, H, n_esp, row_counts_host=None, backward=False) -> float:

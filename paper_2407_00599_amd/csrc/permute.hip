@@ -33,15 +33,17 @@ __device__ __forceinline__ void st8(void* base, int64_t off, const float* f) {
   }
 }
 
-// buf[row,:] = (w?) * x[inv[row]/k, :]  or zeros.  One wave per output row.
+// buf[e, c, :] = (w?) * x[inv[e, c0 + c]/k, :]  or zeros, for the slots c0 <= c0 + c < c0 + Cr of every expert
+// (buf is [E, Cr, M]; the whole buffer when c0 = 0 and Cr = C).  One wave per output row.
 template <bool BF16>
 __global__ __launch_bounds__(256) void dispatch_rows(const void* __restrict__ x, const int32_t* __restrict__ inv,
                                                      const float* __restrict__ w, void* __restrict__ buf,
-                                                     int64_t rows, int M, int k) {
+                                                     int64_t rows, int M, int k, int64_t C, int64_t c0, int64_t Cr) {
   const int lane = threadIdx.x & 63;
   const int64_t row = (int64_t)blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6);
   if (row >= rows) return;
-  const int a = inv[row];
+  const int64_t e = row / Cr;
+  const int a = inv[e * C + c0 + (row - e * Cr)];
   const int64_t dst = row * (int64_t)M;
   if (a < 0) {
     const float z[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
@@ -180,18 +182,26 @@ __global__ __launch_bounds__(256) void combine_dw(const void* __restrict__ dy, c
 
 }  // namespace
 
+extern "C" int moe_dispatch_slots(const void* x, int dtype, int64_t S, int M, int E, int k, int64_t C, int64_t c0,
+                                  int64_t c1, const int32_t* inv, const float* w, void* buf, void* stream) {
+  if (int rc = moe::common_shape_check(S, M, E, k, C)) return rc;
+  MOE_REQUIRE(dtype == MOE_F32 || dtype == MOE_BF16, MOE_EINVAL);
+  MOE_REQUIRE(c0 >= 0 && c0 < c1 && c1 <= C, MOE_EINVAL);
+  MOE_REQUIRE_PTR(x); MOE_REQUIRE_PTR(inv); MOE_REQUIRE_PTR(buf);
+  MOE_OPTIONAL_PTR(w);
+  const int64_t Cr = c1 - c0;
+  const int64_t rows = (int64_t)E * Cr;
+  const dim3 grid((unsigned)((rows + 3) / 4)), block(256);
+  hipStream_t st = (hipStream_t)stream;
+  if (dtype == MOE_BF16) hipLaunchKernelGGL(dispatch_rows<true>, grid, block, 0, st, x, inv, w, buf, rows, M, k, C, c0, Cr);
+  else hipLaunchKernelGGL(dispatch_rows<false>, grid, block, 0, st, x, inv, w, buf, rows, M, k, C, c0, Cr);
+  return moe::check_launch();
+}
+
 extern "C" int moe_dispatch(const void* x, int dtype, int64_t S, int M, int E, int k, int64_t C,
                             const int32_t* inv, const float* w, void* buf, void* stream) {
   if (int rc = moe::common_shape_check(S, M, E, k, C)) return rc;
-  MOE_REQUIRE(dtype == MOE_F32 || dtype == MOE_BF16, MOE_EINVAL);
-  MOE_REQUIRE_PTR(x); MOE_REQUIRE_PTR(inv); MOE_REQUIRE_PTR(buf);
-  MOE_OPTIONAL_PTR(w);
-  const int64_t rows = (int64_t)E * C;
-  const dim3 grid((unsigned)((rows + 3) / 4)), block(256);
-  hipStream_t st = (hipStream_t)stream;
-  if (dtype == MOE_BF16) hipLaunchKernelGGL(dispatch_rows<true>, grid, block, 0, st, x, inv, w, buf, rows, M, k);
-  else hipLaunchKernelGGL(dispatch_rows<false>, grid, block, 0, st, x, inv, w, buf, rows, M, k);
-  return moe::check_launch();
+  return moe_dispatch_slots(x, dtype, S, M, E, k, C, 0, C, inv, w, buf, stream);
 }
 
 extern "C" int moe_combine_fwd(const void* Yret, int dtype, int n_part, int64_t S, int M, int E, int k, int64_t C,
@@ -218,16 +228,16 @@ extern "C" int moe_combine_bwd(const void* dy, const void* Yret, int dtype, int 
   MOE_REQUIRE(dtype == MOE_F32 || dtype == MOE_BF16, MOE_EINVAL);
   MOE_REQUIRE(n_part >= 1 && n_part <= 64, MOE_EINVAL);
   MOE_REQUIRE_PTR(dy); MOE_REQUIRE_PTR(Yret); MOE_REQUIRE_PTR(idx); MOE_REQUIRE_PTR(slot); MOE_REQUIRE_PTR(inv);
-  MOE_REQUIRE_PTR(w); MOE_REQUIRE_PTR(dYret); MOE_REQUIRE_PTR(dw);
+  MOE_REQUIRE_PTR(w); MOE_OPTIONAL_PTR(dYret); MOE_REQUIRE_PTR(dw);
   hipStream_t st = (hipStream_t)stream;
   const int64_t rows = (int64_t)E * C;
   const int64_t ps = rows * M;
   const dim3 block(256), grid_r((unsigned)((rows + 3) / 4)), grid_t((unsigned)((S + 3) / 4));
   if (dtype == MOE_BF16) {
-    hipLaunchKernelGGL(dispatch_rows<true>, grid_r, block, 0, st, dy, inv, w, dYret, rows, M, k);
+    if (dYret) hipLaunchKernelGGL(dispatch_rows<true>, grid_r, block, 0, st, dy, inv, w, dYret, rows, M, k, C, (int64_t)0, C);
     hipLaunchKernelGGL(combine_dw<true>, grid_t, block, 0, st, dy, Yret, idx, slot, dw, S, M, k, C, n_part, ps);
   } else {
-    hipLaunchKernelGGL(dispatch_rows<false>, grid_r, block, 0, st, dy, inv, w, dYret, rows, M, k);
+    if (dYret) hipLaunchKernelGGL(dispatch_rows<false>, grid_r, block, 0, st, dy, inv, w, dYret, rows, M, k, C, (int64_t)0, C);
     hipLaunchKernelGGL(combine_dw<false>, grid_t, block, 0, st, dy, Yret, idx, slot, dw, S, M, k, C, n_part, ps);
   }
   return moe::check_launch();
