@@ -224,6 +224,26 @@ int moe_gate_bwd(const float* dw, const float* w, const int32_t* idx, const floa
                  float* dlogits, float* dWg, float* dgate_bias,
                  void* dx, int dx_accumulate, void* ws, size_t ws_bytes, void* stream);
 
+/* ---------------------------------------------------------------------------------------
+ * Schedule selection, Section V.  Host functions, host pointers, no GPU work.
+ *
+ * moe_alpha_beta_fit: least-squares fit of t = alpha + beta * x to n >= 2 measured (size, time)
+ * pairs of a collective (Section V-A, "Performance Models").  MOE_EINVAL if all sizes are equal.
+ *
+ * moe_choose_schedule: Algorithm 1.  With x = B L M, T = k f B L / E (Section II-A; the listing's
+ * extra factor M in T is taken as a slip, y = E T M N_ESP being the element count it goes on to
+ * use) and y = E T M N_ESP:
+ *     t_D1 = 2 (alpha_a2a + beta_a2a y / N_MP) + alpha_ag_mp + beta_ag_mp x
+ *     t_D2 = alpha_a2a + beta_a2a y / N_MP + alpha_o + beta_o y
+ * Returns 1 (S1, also on a tie) or 2 (S2), or a negative error code; t_d1 / t_d2 (optional)
+ * receive the two times.
+ * --------------------------------------------------------------------------------------- */
+int moe_alpha_beta_fit(const double* x, const double* t, int n, double* alpha, double* beta);
+
+int moe_choose_schedule(double alpha_ag_mp, double beta_ag_mp, double alpha_a2a, double beta_a2a,
+                        double alpha_o, double beta_o, int64_t B, int64_t L, int E, int M, int k,
+                        double f, int n_esp, int n_mp, double* t_d1, double* t_d2);
+
 #ifdef __cplusplus
 }
 #endif

@@ -50,6 +50,11 @@ def lib() -> ctypes.CDLL:
         L.moe_dispatch.argtypes = [c_p, c_i, c_i64, c_i, c_i, c_i, c_i64, c_p, c_p, c_p, c_p]
         L.moe_ffn_workspace_bytes.restype = c_sz
         L.moe_ffn_workspace_bytes.argtypes = [c_i, c_i, c_i, c_i64, c_i, c_i, c_i]
+        L.moe_alpha_beta_fit.restype = c_i
+        L.moe_alpha_beta_fit.argtypes = [c_p, c_p, c_i, c_p, c_p]
+        L.moe_choose_schedule.restype = c_i
+        L.moe_choose_schedule.argtypes = [ctypes.c_double] * 6 + [c_i64, c_i64, c_i, c_i, c_i, ctypes.c_double, c_i, c_i,
+                                          c_p, c_p]
         L.moe_dispatch_slots.restype = c_i
         L.moe_dispatch_slots.argtypes = [c_p, c_i, c_i64, c_i, c_i, c_i, c_i64, c_i64, c_i64, c_p, c_p, c_p, c_p]
         L.moe_ffn_executed_flops.restype = ctypes.c_double
@@ -79,7 +84,8 @@ def lib() -> ctypes.CDLL:
 EXPORTED = [
     "moe_strerror", "moe_abi_version", "moe_capacity", "moe_gate_workspace_bytes", "moe_gate_topk",
     "moe_dispatch", "moe_dispatch_slots", "moe_ffn_workspace_bytes", "moe_ffn_set_tile", "moe_ffn_executed_flops", "moe_expert_ffn_fwd", "moe_expert_ffn_bwd",
-    "moe_combine_fwd", "moe_combine_bwd", "moe_gate_bwd_workspace_bytes", "moe_gate_bwd",
+    "moe_combine_fwd", "moe_combine_bwd", "moe_gate_bwd_workspace_bytes", "moe_gate_bwd", "moe_alpha_beta_fit",
+    "moe_choose_schedule",
 ]
 
 
@@ -151,6 +157,27 @@ def moe_gate_topk(x, Wg, gate_bias, S_total, M, E, k, C, mp_idx, n_mp, norm_topk
 def moe_dispatch(x, S, M, E, k, C, inv, w, buf):
     _check(lib().moe_dispatch(_ptr(x), dtype_code(x), S, M, E, k, C, _ptr(inv), _ptr(w), _ptr(buf), _stream()),
            "moe_dispatch")
+
+
+def moe_alpha_beta_fit(xs, ts):
+    """Host arrays in, (alpha, beta) out."""
+    n = len(xs)
+    ax = (ctypes.c_double * n)(*[float(v) for v in xs])
+    at = (ctypes.c_double * len(ts))(*[float(v) for v in ts])
+    a, b = ctypes.c_double(), ctypes.c_double()
+    _check(lib().moe_alpha_beta_fit(ax, at, min(n, len(ts)) if n == len(ts) else 0, ctypes.byref(a), ctypes.byref(b)),
+           "moe_alpha_beta_fit")
+    return a.value, b.value
+
+
+def moe_choose_schedule(a_ag, b_ag, a_a2a, b_a2a, a_o, b_o, B, L, E, M, k, f, n_esp, n_mp):
+    """Returns (schedule, t_D1, t_D2) with schedule 1 or 2."""
+    t1, t2 = ctypes.c_double(), ctypes.c_double()
+    rc = lib().moe_choose_schedule(a_ag, b_ag, a_a2a, b_a2a, a_o, b_o, B, L, E, M, k, f, n_esp, n_mp, ctypes.byref(t1),
+                                   ctypes.byref(t2))
+    if rc < 0:
+        _check(rc, "moe_choose_schedule")
+    return rc, t1.value, t2.value
 
 
 def moe_dispatch_slots(x, S, M, E, k, C, c0, c1, inv, w, buf):

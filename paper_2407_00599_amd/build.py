@@ -15,7 +15,7 @@ ROOT = os.path.dirname(PKG)
 CSRC = os.path.join(PKG, "csrc")
 OBJ = os.path.join(PKG, "_build")
 LIB = os.path.join(PKG, "libparm_moe.so")
-SOURCES = ["api.hip", "gate.hip", "permute.hip", "ffn.hip", "gate_bwd.hip"]
+SOURCES = ["api.hip", "gate.hip", "permute.hip", "ffn.hip", "gate_bwd.hip", "schedule.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = [
     "-O3", "--offload-arch=gfx950", "-std=c++17", "-fPIC", "-fvisibility=default",
