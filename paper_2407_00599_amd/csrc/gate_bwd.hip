@@ -311,22 +311,217 @@ __global__ __launch_bounds__(128) void gate_dwg_partial_fast(const void* __restr
   if (blockIdx.x == 0 && tid < E && tid < EC) out[(int64_t)M * E + tid] = colsum;
 }
 
-__global__ __launch_bounds__(64) void gate_dwg_reduce(const float* __restrict__ partial, int nchunk, int M, int E,
-                                                      float* __restrict__ dWg, float* __restrict__ dbias) {
-  const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+// dWg[i] = sum over the chunks of partial[chunk][i], in a fixed order: the four waves of a block take
+// every fourth group of four chunks each (four running fp64 sums apiece, so sixteen loads are in flight
+// per output), and wave 0 adds the four results.
+__global__ __launch_bounds__(256) void gate_dwg_reduce(const float* __restrict__ partial, int nchunk, int M, int E,
+                                                       float* __restrict__ dWg, float* __restrict__ dbias) {
+  __shared__ double red[4][64];
+  const int o = threadIdx.x & 63, gq = threadIdx.x >> 6;
+  const int64_t i = (int64_t)blockIdx.x * 64 + o;
   const int64_t n = (int64_t)(M + 1) * E;
-  if (i >= n) return;
-  // eight independent running sums keep eight loads in flight; the order of additions is fixed
-  double s[8] = {0, 0, 0, 0, 0, 0, 0, 0};
-  int c = 0;
-  for (; c + 8 <= nchunk; c += 8) {
+  double s[4] = {0, 0, 0, 0};
+  if (i < n) {
+    int c = gq * 4;
+    for (; c + 20 <= nchunk; c += 32) {   // two of this wave's groups at a time: eight loads in flight
+      float v[8];
 #pragma unroll
-    for (int u = 0; u < 8; ++u) s[u] += (double)partial[(int64_t)(c + u) * n + i];
+      for (int u = 0; u < 4; ++u) {
+        v[u] = partial[(int64_t)(c + u) * n + i];
+        v[4 + u] = partial[(int64_t)(c + 16 + u) * n + i];
+      }
+#pragma unroll
+      for (int u = 0; u < 4; ++u) s[u] += (double)v[u];
+#pragma unroll
+      for (int u = 0; u < 4; ++u) s[u] += (double)v[4 + u];
+    }
+    for (; c < nchunk; c += 16) {
+#pragma unroll
+      for (int u = 0; u < 4; ++u)
+        if (c + u < nchunk) s[u] += (double)partial[(int64_t)(c + u) * n + i];
+    }
   }
-  for (; c < nchunk; ++c) s[0] += (double)partial[(int64_t)c * n + i];
-  const double t = ((s[0] + s[1]) + (s[2] + s[3])) + ((s[4] + s[5]) + (s[6] + s[7]));
-  if (i < (int64_t)M * E) dWg[i] = (float)t;
-  else if (dbias) dbias[i - (int64_t)M * E] = (float)t;
+  red[gq][o] = (s[0] + s[1]) + (s[2] + s[3]);
+  __syncthreads();
+  if (gq == 0 && i < n) {
+    const double t = (red[0][o] + red[1][o]) + (red[2][o] + red[3][o]);
+    if (i < (int64_t)M * E) dWg[i] = (float)t;
+    else if (dbias) dbias[i - (int64_t)M * E] = (float)t;
+  }
+}
+
+// ---------------------------------------------------------------------------------------------
+// E <= 16: the whole gate backward except the final reduction in ONE kernel.  A block owns one
+// chunk of tokens (the unit of a dWg partial sum) and 128 CPT columns of M; a thread owns CPT
+// consecutive columns (CPT = 8 for up to 8 experts, 4 for up to 16, so that its slice of Wg and
+// its dWg accumulators fit in registers).  Sixteen tokens at a time, sixteen threads compute the
+// dlogits rows into LDS (column block 0 also stores them); then every thread reads its x and old
+// dx pieces of those tokens once and uses them twice:
+//     dWg partial[e][q] += x[t, q] dl[t, e]        dx[t, q] (+)= sum_e dl[t, e] Wg[q, e]
+// The partial sums leave through LDS so that [m][e] rows are written contiguously.
+// ---------------------------------------------------------------------------------------------
+constexpr int FT = 16;   // tokens per dlogits stage
+template <bool BF16, int N>
+__device__ __forceinline__ void ldn(const void* base, int64_t off, float* f) {
+  if (N == 8) { ld8g<BF16>(base, off, f); return; }
+  if (BF16) {
+    const uint2 v = *reinterpret_cast<const uint2*>(reinterpret_cast<const bf16_t*>(base) + off);
+    f[0] = __uint_as_float(v.x << 16); f[1] = __uint_as_float(v.x & 0xFFFF0000u);
+    f[2] = __uint_as_float(v.y << 16); f[3] = __uint_as_float(v.y & 0xFFFF0000u);
+  } else {
+    const float4 a = *reinterpret_cast<const float4*>(reinterpret_cast<const float*>(base) + off);
+    f[0] = a.x; f[1] = a.y; f[2] = a.z; f[3] = a.w;
+  }
+}
+template <bool BF16, int N>
+__device__ __forceinline__ void stn(void* base, int64_t off, const float* f) {
+  if (N == 8) { st8g<BF16>(base, off, f); return; }
+  if (BF16) {
+    *reinterpret_cast<uint2*>(reinterpret_cast<bf16_t*>(base) + off) = make_uint2(pack_bf16x2(f[0], f[1]), pack_bf16x2(f[2], f[3]));
+  } else {
+    *reinterpret_cast<float4*>(reinterpret_cast<float*>(base) + off) = make_float4(f[0], f[1], f[2], f[3]);
+  }
+}
+
+// raw (unconverted) CPT elements of a row: requested for all tokens of a stage first, converted when used
+template <bool BF16, int CPT>
+struct RawRow {
+  uint32_t r[BF16 ? CPT / 2 : CPT];
+  __device__ __forceinline__ void load(const void* base, int64_t off) {
+    constexpr int NB = (BF16 ? CPT / 2 : CPT) * 4;   // bytes: 8, 16 or 32
+    const char* p = reinterpret_cast<const char*>(base) + off * (BF16 ? 2 : 4);
+    if (NB == 8) { const uint2 v = *reinterpret_cast<const uint2*>(p); r[0] = v.x; r[1] = v.y; }
+    else {
+#pragma unroll
+      for (int i = 0; i < NB / 16; ++i) {
+        const uint4 v = reinterpret_cast<const uint4*>(p)[i];
+        r[4 * i] = v.x; r[4 * i + 1] = v.y; r[4 * i + 2] = v.z; r[4 * i + 3] = v.w;
+      }
+    }
+  }
+  __device__ __forceinline__ void zero() {
+#pragma unroll
+    for (int i = 0; i < (BF16 ? CPT / 2 : CPT); ++i) r[i] = 0u;
+  }
+  __device__ __forceinline__ float get(int q) const {
+    if (BF16) return __uint_as_float((q & 1) ? (r[q >> 1] & 0xFFFF0000u) : (r[q >> 1] << 16));
+    return __uint_as_float(r[q]);
+  }
+};
+
+template <bool BF16, int EC, int CPT, int NTHR>
+__global__ __launch_bounds__(NTHR) void gate_bwd_fused(const float* __restrict__ dw, const float* __restrict__ w,
+                                                       const int32_t* __restrict__ idx, const float* __restrict__ logits,
+                                                       const void* __restrict__ x, const float* __restrict__ Wg,
+                                                       int64_t S, int M, int E, int k, int norm_topk, int chunk,
+                                                       float* __restrict__ dl_out, void* __restrict__ dx, int accumulate,
+                                                       float* __restrict__ partial) {
+  constexpr int MT = NTHR * CPT, PITCH = MT + 8;
+  __shared__ __attribute__((aligned(16))) float outs[EC * PITCH];
+  __shared__ __attribute__((aligned(16))) float dls[FT * EC];
+  const int tid = threadIdx.x;
+  const int mb = blockIdx.x * MT, ml = tid * CPT, m0 = mb + ml;
+  const bool mok = m0 < M;
+  const int64_t tb = (int64_t)blockIdx.y * chunk;
+  const int64_t te = (tb + chunk < S) ? tb + chunk : S;
+  float* out = partial + (int64_t)blockIdx.y * (M + 1) * E;
+
+  float wr[CPT][EC], acc[EC][CPT];
+#pragma unroll
+  for (int q = 0; q < CPT; ++q)
+#pragma unroll
+    for (int e = 0; e < EC; ++e) {
+      wr[q][e] = (mok && e < E) ? Wg[(int64_t)(m0 + q) * E + e] : 0.f;
+      acc[e][q] = 0.f;
+    }
+  float colsum = 0.f;   // thread e < E of column block 0 sums dl[:, e] for the bias row
+
+  for (int64_t t0 = tb; t0 < te; t0 += FT) {
+    const int nt = (int)((te - t0 < FT) ? te - t0 : FT);
+    // the stage's x and old dx pieces are requested before the dlogits rows are worked out
+    RawRow<BF16, CPT> xr[FT], dr[FT];
+#pragma unroll
+    for (int u = 0; u < FT; ++u) {
+      if (mok && u < nt) xr[u].load(x, (t0 + u) * (int64_t)M + m0); else xr[u].zero();
+      if (mok && u < nt && accumulate) dr[u].load(dx, (t0 + u) * (int64_t)M + m0); else dr[u].zero();
+    }
+    __syncthreads();   // the previous stage's dl rows are consumed
+    if (tid < FT) {
+      const int64_t t = t0 + tid;
+      float row[EC];
+#pragma unroll
+      for (int e = 0; e < EC; ++e) row[e] = 0.f;
+      if (t < te) {
+        float wj[MOE_MAX_K], gj[MOE_MAX_K];
+        int ej[MOE_MAX_K];
+        float inner = 0.f;
+#pragma unroll
+        for (int j = 0; j < MOE_MAX_K; ++j) {
+          wj[j] = 0.f; gj[j] = 0.f; ej[j] = -1;
+          if (j < k) {
+            wj[j] = w[t * k + j]; gj[j] = dw[t * k + j]; ej[j] = idx[t * k + j];
+            inner = fmaf(wj[j], gj[j], inner);
+          }
+        }
+        float mx = 0.f, den = 1.f;
+        if (!norm_topk) {
+          mx = logits[t * E];
+          for (int e = 1; e < E; ++e) mx = fmaxf(mx, logits[t * E + e]);
+          den = 0.f;
+          for (int e = 0; e < E; ++e) den += expf(logits[t * E + e] - mx);
+        }
+#pragma unroll
+        for (int e = 0; e < EC; ++e) {
+          if (e < E) {
+            float v = norm_topk ? 0.f : -(expf(logits[t * E + e] - mx) / den) * inner;
+#pragma unroll
+            for (int j = 0; j < MOE_MAX_K; ++j)
+              if (ej[j] == e) v += norm_topk ? wj[j] * (gj[j] - inner) : wj[j] * gj[j];
+            row[e] = v;
+            if (blockIdx.x == 0) dl_out[t * E + e] = v;
+          }
+        }
+      }
+#pragma unroll
+      for (int e = 0; e < EC; ++e) dls[tid * EC + e] = row[e];
+    }
+    __syncthreads();
+    if (blockIdx.x == 0 && tid < EC)
+      for (int t = 0; t < FT; ++t) colsum += dls[t * EC + tid];
+    if (mok) {
+#pragma unroll
+      for (int u = 0; u < FT; ++u) {
+        float xv[CPT], dv[CPT];
+#pragma unroll
+        for (int q = 0; q < CPT; ++q) { xv[q] = xr[u].get(q); dv[q] = dr[u].get(q); }
+#pragma unroll
+        for (int e4 = 0; e4 < EC; e4 += 4) {
+          const float4 d4 = *reinterpret_cast<const float4*>(&dls[u * EC + e4]);
+          const float d[4] = {d4.x, d4.y, d4.z, d4.w};
+#pragma unroll
+          for (int v = 0; v < 4; ++v)
+#pragma unroll
+            for (int q = 0; q < CPT; ++q) {
+              acc[e4 + v][q] = fmaf(xv[q], d[v], acc[e4 + v][q]);
+              dv[q] = fmaf(d[v], wr[q][e4 + v], dv[q]);
+            }
+        }
+        if (u < nt) stn<BF16, CPT>(dx, (t0 + u) * (int64_t)M + m0, dv);
+      }
+    }
+  }
+  __syncthreads();
+#pragma unroll
+  for (int e = 0; e < EC; ++e)
+#pragma unroll
+    for (int q = 0; q < CPT; q += 4)
+      *reinterpret_cast<float4*>(&outs[e * PITCH + ml + q]) = make_float4(acc[e][q], acc[e][q + 1], acc[e][q + 2], acc[e][q + 3]);
+  __syncthreads();
+  for (int i = tid; i < MT * EC; i += NTHR) {
+    const int m = i / EC, e = i - m * EC;
+    if (mb + m < M && e < E) out[(int64_t)(mb + m) * E + e] = outs[e * PITCH + m];
+  }
+  if (blockIdx.x == 0 && tid < E && tid < EC) out[(int64_t)M * E + tid] = colsum;
 }
 
 }  // namespace
@@ -355,6 +550,22 @@ extern "C" int moe_gate_bwd(const float* dw, const float* w, const int32_t* idx,
   const int norm = norm_topk < 0 ? (k >= 2 ? 1 : 0) : norm_topk;
   hipStream_t st = (hipStream_t)stream;
   const bool bf = x_dtype == MOE_BF16;
+  const int64_t n = (int64_t)(M + 1) * E;
+  if (E <= 16) {   // one fused kernel, then the reduction of the partial sums
+    const int chunk = dwg_chunk(S);
+    const int nchunk = (int)((S + chunk - 1) / chunk);
+    float* partial = (float*)ws;
+    const int cols = E <= 8 ? 256 * 4 : 128 * 4;   // columns per block
+    const dim3 grid((unsigned)((M + cols - 1) / cols), (unsigned)nchunk);
+#define MOE_FUSED(BF, EC, CPT, NT) hipLaunchKernelGGL((gate_bwd_fused<BF, EC, CPT, NT>), grid, dim3(NT), 0, st, dw, w, idx, logits, x, \
+                                                       Wg, S, M, E, k, norm, chunk, dlogits, dx, dx_accumulate, partial)
+    if (bf) { if (E <= 8) MOE_FUSED(true, 8, 4, 256); else MOE_FUSED(true, 16, 4, 128); }
+    else { if (E <= 8) MOE_FUSED(false, 8, 4, 256); else MOE_FUSED(false, 16, 4, 128); }
+#undef MOE_FUSED
+    hipLaunchKernelGGL(gate_dwg_reduce, dim3((unsigned)((n + 63) / 64)), dim3(256), 0, st, partial, nchunk, M, E, dWg,
+                       dgate_bias);
+    return moe::check_launch();
+  }
   hipLaunchKernelGGL(gate_dlogits, dim3((unsigned)((S + 255) / 256)), dim3(256), 0, st, dw, w, idx, logits, S, E, k,
                      norm, dlogits);
   const unsigned gm = (unsigned)((M / 8 + 127) / 128);
@@ -380,8 +591,7 @@ extern "C" int moe_gate_bwd(const float* dw, const float* w, const int32_t* idx,
   if (E <= 16) MOE_GATE_BWD_LAUNCH(gate_dwg_partial_fast, grid_fp, x, dlogits, partial, S, M, E, chunk);
   else MOE_GATE_BWD_LAUNCH(gate_dwg_partial, grid_p, x, dlogits, partial, S, M, E, chunk);
 #undef MOE_GATE_BWD_LAUNCH
-  const int64_t n = (int64_t)(M + 1) * E;
-  hipLaunchKernelGGL(gate_dwg_reduce, dim3((unsigned)((n + 63) / 64)), dim3(64), 0, st, partial, nchunk, M, E, dWg,
+  hipLaunchKernelGGL(gate_dwg_reduce, dim3((unsigned)((n + 63) / 64)), dim3(256), 0, st, partial, nchunk, M, E, dWg,
                      dgate_bias);
   return moe::check_launch();
 }
