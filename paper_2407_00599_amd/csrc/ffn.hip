@@ -215,10 +215,12 @@ __device__ __forceinline__ void store_tile(const GemmArgs& p, f32x16_t (&acc)[MB
 // the XCD; each XCD is given one contiguous range of a linear tile order in which 32 consecutive
 // tiles (what its 32 CUs run at the same time) form an 8 (rows) x 4 (columns) patch of one expert:
 // per k step they share 8 + 4 operand slices in that XCD's L2 instead of 1 + 32.
-__device__ __forceinline__ bool map_tile(const GemmArgs& p, int& g, int& tm, int& tn) {
+// (vb = index of the workgroup within its problem; problems of a merged launch start at multiples of 8,
+// so vb % 8 is still the XCD)
+__device__ __forceinline__ bool map_tile(const GemmArgs& p, int vb, int& g, int& tm, int& tn) {
   constexpr int SW = 4;
   const int per_xcd = (p.total_tiles + 7) / 8;
-  const int tile = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
+  const int tile = (vb & 7) * per_xcd + (vb >> 3);
   if (tile >= p.total_tiles) return false;
   const int tiles_per_g = p.tiles_m * p.tiles_n;
   g = tile / tiles_per_g;
@@ -273,7 +275,7 @@ __global__ __launch_bounds__(WM * WN * 64) void ffn_gemm_bf16(const GemmArgs p) 
   const int wm = wave / WN, wn = wave % WN;
 
   int g, tm, tn;
-  if (!map_tile(p, g, tm, tn)) return;
+  if (!map_tile(p, (int)blockIdx.x, g, tm, tn)) return;
   const int m0 = tm * TM, n0 = tn * TN;
 
   const int64_t b_base = (int64_t)g * p.b_goff + p.b_off;   // weight-type B: start of expert g's slice
@@ -705,22 +707,20 @@ __device__ __forceinline__ void ready(Frag& f) { asm volatile("" : "+v"(f.q)); }
 // WN = waves along n: 2 (4 waves, 128x128 per wave) or 4 (8 waves, 128x64 per wave, two per SIMD).
 // TMR = rows of the output tile: 256, or 192 (three 32-row blocks per wave; only for operands A
 // with k contiguous) for problems whose 256-row tiling would leave many compute units idle.
-template <int KIND, int EPI, int WN, int TMR = 256>
-__global__ __launch_bounds__(128 * WN) void ffn_gemm_dma(const GemmArgs p) {
+template <int KIND, int EPI, int WN, int TMR>
+__device__ __forceinline__ void gemm_dma_tile(const GemmArgs& p, char* smem, int vb) {
   constexpr bool A_NC = (KIND == KIND_TN);                     // A has k as the slow index
   constexpr bool B_NC = (KIND == KIND_NN || KIND == KIND_TN);  // B has k as the slow index
   static_assert(TMR == 256 || (TMR == 192 && !A_NC && WN == 4), "unsupported tile height");
   constexpr int MB = TMR / 64, NBK = 8 / WN;     // 32x32 blocks per wave tile
   constexpr int RPW = 8 / WN;             // requests per wave per operand per k tile (16 in all)
 
-  __shared__ __attribute__((aligned(1024))) char smem[DSTAGES * DSTAGE];
-
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // uniform: keeps LDS bases in SGPRs
   const int wm = wave / WN, wn = wave % WN;
 
   int g, tm, tn;
-  if (!map_tile(p, g, tm, tn)) return;
+  if (!map_tile(p, vb, g, tm, tn)) return;
   const int m0 = tm * TMR, n0 = tn * DT;
 
   const int64_t b_base = (int64_t)g * p.b_goff + p.b_off;
@@ -967,6 +967,25 @@ __global__ __launch_bounds__(128 * WN) void ffn_gemm_dma(const GemmArgs p) {
                                  n0 + wn * (32 * NBK), lane);
 }
 
+template <int KIND, int EPI, int WN, int TMR = 256>
+__global__ __launch_bounds__(128 * WN) void ffn_gemm_dma(const GemmArgs p) {
+  __shared__ __attribute__((aligned(1024))) char smem[DSTAGES * DSTAGE];
+  gemm_dma_tile<KIND, EPI, WN, TMR>(p, smem, (int)blockIdx.x);
+}
+
+// The three GEMMs of the backward pass that only depend on dZ, in one launch: dX = dZ W1^T (row-tiled,
+// the long tiles, first in the grid) and the two weight gradients.  nbx and nbw are the (multiple-of-8)
+// workgroup counts of the first two problems.
+template <int TMR_X>
+__global__ __launch_bounds__(512) void ffn_bwd_trio(const GemmArgs px, const GemmArgs pw2, const GemmArgs pw1, int nbx,
+                                                    int nbw) {
+  __shared__ __attribute__((aligned(1024))) char smem[DSTAGES * DSTAGE];
+  const int b = (int)blockIdx.x;
+  if (b < nbx) gemm_dma_tile<KIND_NT, EPI_STORE, 4, TMR_X>(px, smem, b);
+  else if (b < nbx + nbw) gemm_dma_tile<KIND_TN, EPI_STORE, 4, 256>(pw2, smem, b - nbx);
+  else gemm_dma_tile<KIND_TN, EPI_STORE, 4, 256>(pw1, smem, b - nbx - nbw);
+}
+
 // ------------------------------------------------------------------------------------------
 // fp32 kernel: 64x64 tile, 256 threads, 4x4 outputs per thread, fp64 accumulation.
 // ------------------------------------------------------------------------------------------
@@ -1103,6 +1122,19 @@ TilePlan plan_tiles(bool tn, int G, int Mdim, int Ndim) {
   return t;
 }
 
+// fills the tile counts and buffer sizes of a bf16 problem
+TilePlan prepare_bf16(GemmArgs& a, bool tn) {
+  a.kchunks = (a.Cc + KT - 1) / KT;
+  const uint64_t act_rows = (uint64_t)a.n_src * a.G * a.Cc;
+  a.a_bytes = act_rows * (uint64_t)a.lda * 2;
+  a.b_bytes = tn ? act_rows * (uint64_t)a.ldb * 2 : (uint64_t)a.G * (uint64_t)a.b_goff * 2;
+  const TilePlan t = plan_tiles(tn, a.G, a.Mdim, a.Ndim);
+  a.tiles_n = (a.Ndim + t.tile_n - 1) / t.tile_n;
+  a.tiles_m = (a.Mdim + t.tile_m - 1) / t.tile_m;
+  a.total_tiles = a.G * a.tiles_m * a.tiles_n;
+  return t;
+}
+
 template <int KIND, int EPI>
 void launch_gemm(GemmArgs a, int dtype, hipStream_t st) {
   if (dtype == MOE_F32) {
@@ -1112,14 +1144,7 @@ void launch_gemm(GemmArgs a, int dtype, hipStream_t st) {
     hipLaunchKernelGGL((ffn_gemm_f32<KIND, EPI>), dim3(a.total_tiles), dim3(256), 0, st, a);
     return;
   }
-  a.kchunks = (a.Cc + KT - 1) / KT;
-  const uint64_t act_rows = (uint64_t)a.n_src * a.G * a.Cc;
-  a.a_bytes = act_rows * (uint64_t)a.lda * 2;
-  a.b_bytes = (KIND == KIND_TN) ? act_rows * (uint64_t)a.ldb * 2 : (uint64_t)a.G * (uint64_t)a.b_goff * 2;
-  const TilePlan t = plan_tiles(KIND == KIND_TN, a.G, a.Mdim, a.Ndim);
-  a.tiles_n = (a.Ndim + t.tile_n - 1) / t.tile_n;
-  a.tiles_m = (a.Mdim + t.tile_m - 1) / t.tile_m;
-  a.total_tiles = a.G * a.tiles_m * a.tiles_n;
+  const TilePlan t = prepare_bf16(a, KIND == KIND_TN);
   const dim3 grid((unsigned)(((a.total_tiles + 7) / 8) * 8));
   if (t.tile_m == 192) {
     if constexpr (KIND != KIND_TN) hipLaunchKernelGGL((ffn_gemm_dma<KIND, EPI, 4, 192>), grid, dim3(512), 0, st, a);
@@ -1258,22 +1283,37 @@ extern "C" int moe_expert_ffn_bwd(const void* dY, const void* X, const void* Z, 
   a.Mdim = a.R; a.Ndim = Hl; a.Kdim = M;
   launch_gemm<KIND_NT, EPI_DGELU>(a, dtype, st);
   // dW2[h0:h0+Hl, :] = Act^T * dY
-  a.A = Act; a.lda = Hl;
-  a.B = dY; a.ldb = M;
-  a.C = dW2; a.C2 = nullptr; a.Zin = nullptr; a.ldc = M; a.c_goff = (int64_t)H * M; a.c_off = h0 * M;
-  a.Mdim = Hl; a.Ndim = M; a.Kdim = a.R;
-  launch_gemm<KIND_TN, EPI_STORE>(a, dtype, st);
+  GemmArgs w2 = a;
+  w2.A = Act; w2.lda = Hl;
+  w2.B = dY; w2.ldb = M;
+  w2.C = dW2; w2.C2 = nullptr; w2.Zin = nullptr; w2.ldc = M; w2.c_goff = (int64_t)H * M; w2.c_off = h0 * M;
+  w2.Mdim = Hl; w2.Ndim = M; w2.Kdim = a.R;
   // dW1[:, h0:h0+Hl] = X^T * dZ
-  a.A = X; a.lda = M;
-  a.B = dZ; a.ldb = Hl;
-  a.C = dW1; a.ldc = H; a.c_goff = (int64_t)M * H; a.c_off = h0;
-  a.Mdim = M; a.Ndim = Hl; a.Kdim = a.R;
-  launch_gemm<KIND_TN, EPI_STORE>(a, dtype, st);
+  GemmArgs w1 = w2;
+  w1.A = X; w1.lda = M;
+  w1.B = dZ; w1.ldb = Hl;
+  w1.C = dW1; w1.ldc = H; w1.c_goff = (int64_t)M * H; w1.c_off = h0;
+  w1.Mdim = M; w1.Ndim = Hl; w1.Kdim = a.R;
   // dX = dZ * W1[:, h0:h0+Hl]^T
-  a.A = dZ; a.lda = Hl;
-  a.B = W1; a.ldb = H; a.b_goff = (int64_t)M * H; a.b_off = h0;
-  a.C = dX; a.ldc = M; a.c_goff = 0; a.c_off = 0;
-  a.Mdim = a.R; a.Ndim = M; a.Kdim = Hl;
-  launch_gemm<KIND_NT, EPI_STORE>(a, dtype, st);
+  GemmArgs dx = w1;
+  dx.A = dZ; dx.lda = Hl;
+  dx.B = W1; dx.ldb = H; dx.b_goff = (int64_t)M * H; dx.b_off = h0;
+  dx.C = dX; dx.ldc = M; dx.c_goff = 0; dx.c_off = 0;
+  dx.Mdim = a.R; dx.Ndim = M; dx.Kdim = Hl;
+  if (dtype == MOE_BF16 && (g_tile_pref == 0 || g_tile_pref == 6 || g_tile_pref == 7)) {
+    // the three are independent: one launch, long row tiles first, if all of them take the 8-wave kernel
+    GemmArgs px = dx, p2 = w2, p1 = w1;
+    const TilePlan tx = prepare_bf16(px, false), t2 = prepare_bf16(p2, true), t1 = prepare_bf16(p1, true);
+    if (tx.dma && t2.dma && t1.dma) {
+      const int nbx = (px.total_tiles + 7) / 8 * 8, nb2 = (p2.total_tiles + 7) / 8 * 8, nb1 = (p1.total_tiles + 7) / 8 * 8;
+      const dim3 grid((unsigned)(nbx + nb2 + nb1));
+      if (tx.tile_m == 192) hipLaunchKernelGGL((ffn_bwd_trio<192>), grid, dim3(512), 0, st, px, p2, p1, nbx, nb2);
+      else hipLaunchKernelGGL((ffn_bwd_trio<256>), grid, dim3(512), 0, st, px, p2, p1, nbx, nb2);
+      return moe::check_launch();
+    }
+  }
+  launch_gemm<KIND_TN, EPI_STORE>(w2, dtype, st);
+  launch_gemm<KIND_TN, EPI_STORE>(w1, dtype, st);
+  launch_gemm<KIND_NT, EPI_STORE>(dx, dtype, st);
   return moe::check_launch();
 }
