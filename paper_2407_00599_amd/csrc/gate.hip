@@ -49,23 +49,25 @@ __device__ __forceinline__ double shfl_xor_f64(double v, int mask) {
   return __hiloint2double(hi, lo);
 }
 
-// EC = experts held per lane (E <= EC), T = 64/EC tokens per wave, 8 waves per block.
-// The block walks M in chunks of 512.  Per chunk it converts Wg[chunk, :] to fp64 once into LDS
-// (shared by the 8 T tokens of the block, laid out [8][64 lanes][EC] so that a lane's EC doubles are
-// contiguous and lanes are adjacent: conflict-free), each lane takes 8 consecutive m of every one of
-// its wave's T tokens (16-byte loads of x, the next chunk requested before this one is multiplied)
-// and runs T*EC fp64 FMAs per m.
-template <int EC, bool BF16>
-__global__ __launch_bounds__(512) void gate_logits_small_e(const void* __restrict__ x, const float* __restrict__ Wg,
-                                                            const float* __restrict__ bias, float* __restrict__ logits,
-                                                            int64_t S, int M, int E) {
-  constexpr int T = 64 / EC;
+// EC = experts held per lane (E <= EC), T tokens per wave, NW waves per block (T EC a power of two <= 64).
+// The block walks M in chunks of 512.  Per chunk it converts Wg[chunk, :] to fp64 once into LDS (shared by
+// the NW T tokens of the block, laid out [8][64 lanes][EC] so that a lane's EC doubles are contiguous),
+// each lane takes 8 consecutive m of every one of its wave's T tokens
+// (16-byte loads of x, the next chunk requested before this one is multiplied) and runs T*EC fp64 FMAs per
+// m.  Blocks are small (4 waves, 4 or 2 tokens per wave) and light on registers so that several are
+// resident per compute unit: one block's barriers and Wg staging hide behind another's FMAs.
+template <int EC, bool BF16, int T, int NW>
+__global__ __launch_bounds__(64 * NW) void gate_logits_small_e(const void* __restrict__ x, const float* __restrict__ Wg,
+                                                               const float* __restrict__ bias, float* __restrict__ logits,
+                                                               int64_t S, int M, int E) {
+  constexpr int NOUT = T * EC;
+  static_assert(NOUT >= 2 && NOUT <= 64 && (NOUT & (NOUT - 1)) == 0, "T * EC must be a power of two <= 64");
   __shared__ double Ws[8 * 64 * EC];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int64_t t0 = ((int64_t)blockIdx.x * 8 + wave) * T;
-  double acc[T * EC];
+  const int64_t t0 = ((int64_t)blockIdx.x * NW + wave) * T;
+  double acc[NOUT];
 #pragma unroll
-  for (int i = 0; i < T * EC; ++i) acc[i] = 0.0;
+  for (int i = 0; i < NOUT; ++i) acc[i] = 0.0;
 
   typedef uint4 XRaw[BF16 ? 1 : 2];
   XRaw xr[T], xn[T];
@@ -83,17 +85,20 @@ __global__ __launch_bounds__(512) void gate_logits_small_e(const void* __restric
       }
     }
   };
-  if (BF16) load_x(xr, lane * 8);
+  load_x(xr, lane * 8);
   for (int mb = 0; mb < M; mb += 512) {
-    if (!BF16) load_x(xr, mb + lane * 8);   // fp32 rows are twice as wide: no register room for a prefetch
     __syncthreads();  // previous chunk's Ws fully consumed
-    for (int i = tid; i < 512 * EC; i += 512) {
-      const int m = i / EC, e = i - m * EC;           // m = lane' * 8 + mm
-      const float wv = (mb + m < M && e < E) ? Wg[(int64_t)(mb + m) * E + e] : 0.f;
-      Ws[(((m & 7) * 64) + (m >> 3)) * EC + e] = (double)wv;
+    // slot i of the chunk, laid out [mm][expert pair][lane][2]: 16-byte reads at a 16-byte lane stride
+    // slot i of the chunk holds expert i % EC of row m = 8 (i / EC % 64) + i / (64 EC): LDS writes are
+    // contiguous (the Wg reads, 32-byte pieces, come from L2)
+    for (int i = tid; i < 512 * EC; i += 64 * NW) {
+      const int e = i % EC, lp = (i / EC) & 63, mm = i / (64 * EC);
+      const int m = mb + lp * 8 + mm;
+      Ws[i] = (double)((m < M && e < E) ? Wg[(int64_t)m * E + e] : 0.f);
     }
     __syncthreads();
-    if (BF16 && mb + 512 < M) load_x(xn, mb + 512 + lane * 8);
+    const bool more = mb + 512 < M;
+    if (more) load_x(xn, mb + 512 + lane * 8);
 #pragma unroll
     for (int mm = 0; mm < 8; ++mm) {
       double wd[EC];
@@ -113,25 +118,37 @@ __global__ __launch_bounds__(512) void gate_logits_small_e(const void* __restric
         for (int e = 0; e < EC; ++e) acc[t * EC + e] = fma(xd, wd[e], acc[t * EC + e]);
       }
     }
-    if (BF16 && mb + 512 < M) {
+    if (more) {
 #pragma unroll
-      for (int t = 0; t < T; ++t) xr[t][0] = xn[t][0];
+      for (int t = 0; t < T; ++t) {
+        xr[t][0] = xn[t][0];
+        if (!BF16) xr[t][BF16 ? 0 : 1] = xn[t][BF16 ? 0 : 1];
+      }
     }
   }
-  // halving reduction over the 64 lanes: after the step with mask h, a lane whose bit h is
-  // set holds the upper half of the value list; at the end lane i holds the sum of value i.
+  // halving reduction over the lanes: after the step with lane mask lm a lane whose bit lm is set holds
+  // the upper half of its value list, summed with its partner's; once a single value is left the
+  // remaining lane bits are plain butterfly sums.  At the end lane l holds value l >> log2(64 / NOUT).
 #pragma unroll
-  for (int h = 32; h >= 1; h >>= 1) {
-    const bool up = (lane & h) != 0;
+  for (int st = 0; st < 6; ++st) {
+    const int lm = 32 >> st;
+    if ((NOUT >> st) > 1) {
+      const int h = NOUT >> (st + 1);
+      const bool up = (lane & lm) != 0;
 #pragma unroll
-    for (int i = 0; i < h; ++i) {
-      const double keep = up ? acc[i + h] : acc[i];
-      const double send = up ? acc[i] : acc[i + h];
-      acc[i] = keep + shfl_xor_f64(send, h);
+      for (int i = 0; i < h; ++i) {
+        const double keep = up ? acc[i + h] : acc[i];
+        const double send = up ? acc[i] : acc[i + h];
+        acc[i] = keep + shfl_xor_f64(send, lm);
+      }
+    } else {
+      acc[0] += shfl_xor_f64(acc[0], lm);
     }
   }
-  const int t = lane / EC, e = lane % EC;
-  if (t0 + t < S && e < E) {
+  constexpr int REP = 64 / NOUT;          // lanes holding the same value
+  const int o = lane / REP;
+  const int t = o / EC, e = o % EC;
+  if (lane % REP == 0 && t0 + t < S && e < E) {
     double v = acc[0];
     if (bias) v += (double)bias[e];
     logits[(t0 + t) * E + e] = (float)v;
@@ -423,12 +440,12 @@ extern "C" int moe_gate_topk(const void* x, int x_dtype, const float* Wg, const 
     const void* xs = (const char*)x + (size_t)mp_idx * S * M * esz;
     if (E <= 16) {
       const int EC = E <= 8 ? 8 : 16;
-      const int T = 64 / EC;
-      const dim3 grid((unsigned)((S + 8 * T - 1) / (8 * T))), block(512);
-#define LAUNCH_SMALL(ec) do { \
-    if (bf) hipLaunchKernelGGL((gate_logits_small_e<ec, true>), grid, block, 0, st, xs, Wg, gate_bias, logits, S, M, E); \
-    else hipLaunchKernelGGL((gate_logits_small_e<ec, false>), grid, block, 0, st, xs, Wg, gate_bias, logits, S, M, E); } while (0)
-      if (EC == 8) LAUNCH_SMALL(8); else LAUNCH_SMALL(16);
+      const int T = E <= 8 ? 4 : 2;
+      const dim3 grid((unsigned)((S + 4 * T - 1) / (4 * T))), block(256);
+#define LAUNCH_SMALL(ec, t) do { \
+    if (bf) hipLaunchKernelGGL((gate_logits_small_e<ec, true, t, 4>), grid, block, 0, st, xs, Wg, gate_bias, logits, S, M, E); \
+    else hipLaunchKernelGGL((gate_logits_small_e<ec, false, t, 4>), grid, block, 0, st, xs, Wg, gate_bias, logits, S, M, E); } while (0)
+      if (EC == 8) LAUNCH_SMALL(8, 4); else LAUNCH_SMALL(16, 2);
 #undef LAUNCH_SMALL
     } else {
       const dim3 grid((unsigned)((S + 63) / 64), (unsigned)((E + 63) / 64)), block(256);
