@@ -57,7 +57,7 @@ __device__ __forceinline__ double shfl_xor_f64(double v, int mask) {
 // m.  Blocks are small (4 waves, 4 or 2 tokens per wave) and light on registers so that several are
 // resident per compute unit: one block's barriers and Wg staging hide behind another's FMAs.
 template <int EC, bool BF16, int T, int NW>
-__global__ __launch_bounds__(64 * NW) void gate_logits_small_e(const void* __restrict__ x, const float* __restrict__ Wg,
+__global__ __launch_bounds__(64 * NW, NW == 8 ? 4 : 1) void gate_logits_small_e(const void* __restrict__ x, const float* __restrict__ Wg,
                                                                const float* __restrict__ bias, float* __restrict__ logits,
                                                                int64_t S, int M, int E) {
   constexpr int NOUT = T * EC;
@@ -441,9 +441,12 @@ extern "C" int moe_gate_topk(const void* x, int x_dtype, const float* Wg, const 
     if (E <= 16) {
       const int EC = E <= 8 ? 8 : 16;
       const int T = E <= 8 ? 4 : 2;
-      const dim3 grid((unsigned)((S + 4 * T - 1) / (4 * T))), block(256);
+      // many tokens: 8-wave blocks halve the Wg staging work per token; few tokens: 4-wave blocks fill the chip
+      const int nw = (S >= 16384 && bf) ? 8 : 4;
+      const dim3 grid((unsigned)((S + nw * T - 1) / (nw * T))), block(64 * nw);
 #define LAUNCH_SMALL(ec, t) do { \
-    if (bf) hipLaunchKernelGGL((gate_logits_small_e<ec, true, t, 4>), grid, block, 0, st, xs, Wg, gate_bias, logits, S, M, E); \
+    if (bf && nw == 8) hipLaunchKernelGGL((gate_logits_small_e<ec, true, t, 8>), grid, block, 0, st, xs, Wg, gate_bias, logits, S, M, E); \
+    else if (bf) hipLaunchKernelGGL((gate_logits_small_e<ec, true, t, 4>), grid, block, 0, st, xs, Wg, gate_bias, logits, S, M, E); \
     else hipLaunchKernelGGL((gate_logits_small_e<ec, false, t, 4>), grid, block, 0, st, xs, Wg, gate_bias, logits, S, M, E); } while (0)
       if (EC == 8) LAUNCH_SMALL(8, 4); else LAUNCH_SMALL(16, 2);
 #undef LAUNCH_SMALL
