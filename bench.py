@@ -5,8 +5,8 @@
 
 A step is one pass of the whole hot path over one batch of seeded synthetic input that is
 already resident in HBM.  Prints ONE JSON line: tokens/s of the layer fwd+bwd, the roofline of
-the dominant kernel family (the grouped bf16 MFMA GEMMs of the expert FFN: flops per launch /
-mean launch time, timed with HIP events on the launch stream inside the timed steps) and the
+the dominant kernel family (the six grouped bf16 MFMA GEMMs of the expert FFN: executed flops per GEMM /
+mean time per GEMM, timed with HIP events on the launch stream inside the timed steps) and the
 CPU checker timed on the host cores on the same workload.
 """
 import argparse
@@ -20,9 +20,9 @@ sys.path.insert(0, ROOT)
 
 MFMA_BF16_PEAK_TFLOPS = 2500.0   # MI355X dense bf16 matrix peak
 HBM_PEAK_GBS = 8000.0
-# HBM bytes per GEMM launch (mean of the 6 launches), from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of
+# HBM bytes per grouped GEMM (mean of the 6 per step), from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of
 # this command scaled by the copy calibration; None where no such run has been made (see profiles/).
-MEASURED_TRAFFIC = {"layer_bf16": 215.3e6}   # profiles/bench_layer_bf16_gemm_pmc.md
+MEASURED_TRAFFIC = {"layer_bf16": 228.1e6}   # profiles/bench_layer_bf16_gemm_pmc.md
 
 
 def main():
@@ -140,12 +140,12 @@ def main():
     achieved = flops_per_launch / (gemm_ms * 1e-3) / 1e12
     roofline = {"bound": "mfma", "achieved": round(achieved, 2), "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
                 "frac": round(achieved / MFMA_BF16_PEAK_TFLOPS, 4), "traffic": MEASURED_TRAFFIC.get(cfg.name),
-                "kernel": "ffn_gemm_dma (6 launches per step)", "launch_ms": round(gemm_ms, 4),
-                "flops_per_launch": flops_per_launch, "occupied_rows": occupied, "capacity_rows": rows,
+                "kernel": "ffn_gemm_dma x3 + ffn_bwd_trio (6 grouped GEMMs in 4 launches per step)", "gemm_ms": round(gemm_ms, 4),
+                "flops_per_gemm": flops_per_launch, "occupied_rows": occupied, "capacity_rows": rows,
                 "flops_if_all_capacity_rows": 2.0 * rows * cfg.M * L.Hl}
     if cfg.dtype == "f32":
         roofline.update({"bound": "alu", "peak": 78.6, "frac": round(achieved / 78.6, 5),
-                         "kernel": "ffn_gemm_f32 (6 launches per step)"})
+                         "kernel": "ffn_gemm_f32 (6 grouped GEMMs per step)"})
 
     cpu = None
     if small and not args.no_cpu_baseline and L.closed:
