@@ -6,8 +6,8 @@
 //                         once, coalesced, 16 B per lane; Wg goes through LDS as fp64, shared
 //                         by the 8 waves of a block.  fp64 accumulation, then a halving
 //                         cross-lane reduction that leaves lane i with output i.
-//   gate_logits_tiled   : any E.  64 tokens x 64 experts per block, LDS-staged K chunks,
-//                         4x4 register tile per thread, fp64 accumulation.
+//   gate_logits_mfma    : E > 16.  64 tokens x 64 experts per block on the fp64 matrix cores
+//                         (v_mfma_f64_16x16x4_f64), K chunks converted to fp64 on their way into LDS.
 //   gate_topk           : a group of W = pow2 >= E lanes per token; k rounds of an arg-max
 //                         butterfly (ties -> lower expert index); softmax weights; per-block
 //                         (choice, expert) histogram for the slot scan.
@@ -155,60 +155,91 @@ __global__ __launch_bounds__(64 * NW, NW == 8 ? 4 : 1) void gate_logits_small_e(
   }
 }
 
-// 64 tokens x 64 experts per block; thread (ty,tx) owns tokens ty*4..+4, experts tx*4..+4.
+// E > 16: fp64 matrix cores.  v_mfma_f64_16x16x4_f64 multiplies a 16 x 4 by a 4 x 16 tile of doubles (lane l
+// supplies A[l % 16][l / 16] and B[l / 16][l % 16], and receives D[4 r + l / 16][l % 16], r = 0..3).  A block of
+// 4 waves owns 64 tokens x 64 experts (grid.y walks the expert blocks), a wave 16 tokens x 64 experts (four
+// accumulator tiles).  M is walked in chunks of 32: x and Wg are converted to fp64 once on their way into LDS
+// ([k][token] and [k][expert], pitch 80 doubles so that the two k planes of a 32-lane access fall into
+// different banks), the next chunk's raw data being requested before the current one is multiplied.
+typedef double f64x4_t __attribute__((ext_vector_type(4)));
+constexpr int LM_KC = 32, LM_PITCH = 80;
 template <bool BF16>
-__global__ __launch_bounds__(256) void gate_logits_tiled(const void* __restrict__ x, const float* __restrict__ Wg,
-                                                         const float* __restrict__ bias, float* __restrict__ logits,
-                                                         int64_t S, int M, int E) {
-  constexpr int KC = 32;
-  __shared__ float xs[KC][64 + 4];   // [k][token]
-  __shared__ float wsm[KC][64 + 4];  // [k][expert]
-  const int tid = threadIdx.x;
-  const int tx = tid & 15, ty = tid >> 4;
-  const int64_t t0 = (int64_t)blockIdx.x * 64;
+__global__ __launch_bounds__(256) void gate_logits_mfma(const void* __restrict__ x, const float* __restrict__ Wg,
+                                                        const float* __restrict__ bias, float* __restrict__ logits,
+                                                        int64_t S, int M, int E) {
+  __shared__ double xs[LM_KC * LM_PITCH];
+  __shared__ double ws[LM_KC * LM_PITCH];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int64_t tb = (int64_t)blockIdx.x * 64;
   const int e0 = blockIdx.y * 64;
-  double acc[4][4];
+  // staging roles: x -> token tid / 4, k offset 8 (tid % 4); Wg -> k row tid / 8, experts 8 (tid % 8)
+  const int xt = tid >> 2, xk = (tid & 3) * 8;
+  const int wk = tid >> 3, we = (tid & 7) * 8;
+  uint4 xraw[BF16 ? 1 : 2];
+  float4 wraw[2];
+  auto fetch = [&](int k0) {
+    const bool xok = (tb + xt < S) && (k0 + xk < M);     // M % 8 == 0: the 8 elements are in or out together
+    const int64_t xo = (tb + xt) * (int64_t)M + k0 + xk;
+    if (BF16) {
+      xraw[0] = xok ? *reinterpret_cast<const uint4*>(reinterpret_cast<const bf16_t*>(x) + xo) : make_uint4(0, 0, 0, 0);
+    } else {
+      const uint4* p = reinterpret_cast<const uint4*>(reinterpret_cast<const float*>(x) + xo);
+      xraw[0] = xok ? p[0] : make_uint4(0, 0, 0, 0);
+      xraw[BF16 ? 0 : 1] = xok ? p[1] : make_uint4(0, 0, 0, 0);
+    }
+    const bool kok = k0 + wk < M;
+    const float* wp = Wg + (int64_t)(k0 + wk) * E + e0 + we;
+    float wv[8];
 #pragma unroll
-  for (int i = 0; i < 4; ++i)
+    for (int u = 0; u < 8; ++u) wv[u] = (kok && e0 + we + u < E) ? wp[u] : 0.f;   // E need not be a multiple of 4
+    wraw[0] = make_float4(wv[0], wv[1], wv[2], wv[3]);
+    wraw[1] = make_float4(wv[4], wv[5], wv[6], wv[7]);
+  };
+  auto stage = [&]() {
+    float xf[8];
+    if (BF16) {
+      unpack_bf16x8(xraw[0], xf);
+    } else {
+      xf[0] = __uint_as_float(xraw[0].x); xf[1] = __uint_as_float(xraw[0].y); xf[2] = __uint_as_float(xraw[0].z);
+      xf[3] = __uint_as_float(xraw[0].w); xf[4] = __uint_as_float(xraw[BF16 ? 0 : 1].x); xf[5] = __uint_as_float(xraw[BF16 ? 0 : 1].y);
+      xf[6] = __uint_as_float(xraw[BF16 ? 0 : 1].z); xf[7] = __uint_as_float(xraw[BF16 ? 0 : 1].w);
+    }
 #pragma unroll
-    for (int j = 0; j < 4; ++j) acc[i][j] = 0.0;
+    for (int u = 0; u < 8; ++u) xs[(xk + u) * LM_PITCH + xt] = (double)xf[u];
+    const float wv[8] = {wraw[0].x, wraw[0].y, wraw[0].z, wraw[0].w, wraw[1].x, wraw[1].y, wraw[1].z, wraw[1].w};
+#pragma unroll
+    for (int u = 0; u < 8; ++u) ws[wk * LM_PITCH + we + u] = (double)wv[u];
+  };
+  f64x4_t acc[4];
+#pragma unroll
+  for (int j = 0; j < 4; ++j) acc[j] = f64x4_t{0.0, 0.0, 0.0, 0.0};
 
-  for (int k0 = 0; k0 < M; k0 += KC) {
-    {  // x tile: 64 tokens x 32 k = 256 groups of 8 consecutive k
-      const int tok = tid >> 2, kq = (tid & 3) * 8;
-      float f[8];
-      load8<BF16>(x, (t0 + tok) * (int64_t)M + k0 + kq, (t0 + tok < S) && (k0 + kq < M), f);
-#pragma unroll
-      for (int i = 0; i < 8; ++i) xs[kq + i][tok] = f[i];
-    }
-#pragma unroll
-    for (int i = 0; i < 8; ++i) {  // Wg tile: 32 k x 64 experts
-      const int c = tid + i * 256;
-      const int kk = c >> 6, ee = c & 63;
-      wsm[kk][ee] = (k0 + kk < M && e0 + ee < E) ? Wg[(int64_t)(k0 + kk) * E + e0 + ee] : 0.f;
-    }
+  fetch(0);
+  for (int k0 = 0; k0 < M; k0 += LM_KC) {
+    __syncthreads();   // the previous chunk is consumed
+    stage();
     __syncthreads();
-#pragma unroll 8
-    for (int kk = 0; kk < KC; ++kk) {
-      const float4 xv = *reinterpret_cast<const float4*>(&xs[kk][ty * 4]);
-      const float4 wv = *reinterpret_cast<const float4*>(&wsm[kk][tx * 4]);
-      const double xd[4] = {(double)xv.x, (double)xv.y, (double)xv.z, (double)xv.w};
-      const double wd[4] = {(double)wv.x, (double)wv.y, (double)wv.z, (double)wv.w};
+    if (k0 + LM_KC < M) fetch(k0 + LM_KC);
 #pragma unroll
-      for (int i = 0; i < 4; ++i)
+    for (int s4 = 0; s4 < LM_KC / 4; ++s4) {
+      const int kr = (4 * s4 + (lane >> 4)) * LM_PITCH;
+      const double a = xs[kr + wave * 16 + (lane & 15)];
 #pragma unroll
-        for (int j = 0; j < 4; ++j) acc[i][j] = fma(xd[i], wd[j], acc[i][j]);
+      for (int j = 0; j < 4; ++j) {
+        const double bv = ws[kr + j * 16 + (lane & 15)];
+        acc[j] = __builtin_amdgcn_mfma_f64_16x16x4f64(a, bv, acc[j], 0, 0, 0);
+      }
     }
-    __syncthreads();
   }
 #pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    const int64_t t = t0 + ty * 4 + i;
-    if (t >= S) continue;
+  for (int j = 0; j < 4; ++j) {
+    const int e = e0 + j * 16 + (lane & 15);
+    if (e >= E) continue;
+    const double bj = bias ? (double)bias[e] : 0.0;
 #pragma unroll
-    for (int j = 0; j < 4; ++j) {
-      const int e = e0 + tx * 4 + j;
-      if (e < E) logits[t * E + e] = (float)(acc[i][j] + (bias ? (double)bias[e] : 0.0));
+    for (int r = 0; r < 4; ++r) {
+      const int64_t t = tb + wave * 16 + 4 * r + (lane >> 4);
+      if (t < S) logits[t * E + e] = (float)(acc[j][r] + bj);
     }
   }
 }
@@ -452,8 +483,8 @@ extern "C" int moe_gate_topk(const void* x, int x_dtype, const float* Wg, const 
 #undef LAUNCH_SMALL
     } else {
       const dim3 grid((unsigned)((S + 63) / 64), (unsigned)((E + 63) / 64)), block(256);
-      if (bf) hipLaunchKernelGGL((gate_logits_tiled<true>), grid, block, 0, st, xs, Wg, gate_bias, logits, S, M, E);
-      else hipLaunchKernelGGL((gate_logits_tiled<false>), grid, block, 0, st, xs, Wg, gate_bias, logits, S, M, E);
+      if (bf) hipLaunchKernelGGL((gate_logits_mfma<true>), grid, block, 0, st, xs, Wg, gate_bias, logits, S, M, E);
+      else hipLaunchKernelGGL((gate_logits_mfma<false>), grid, block, 0, st, xs, Wg, gate_bias, logits, S, M, E);
     }
   }
   if (E <= 1) launch_topk<1, 1>(logits, S, E, k, norm, idx, w, blockhist, nblk, st);

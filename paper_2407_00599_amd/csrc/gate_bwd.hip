@@ -1,25 +1,26 @@
 // Backward of the gating function of Section II-A (linear layer + softmax + top-k), with the
 // top-k selection held fixed.
 //
-//   gate_dlogits : one thread per token.  norm_topk: dl[e_j] = w_j (dw_j - sum_j' w_j' dw_j');
-//                  otherwise dl[e] = sum_j dw_j p[e_j] (delta(e,e_j) - p[e]) with p = softmax(l).
-//   gate_dx      : dx[t,m] (+)= sum_e dl[t,e] Wg[m,e].  A thread owns 8 consecutive m and keeps
-//                  16 experts of Wg in registers while it walks over its tokens; dl rows are
-//                  uniform per token.  Bound by the dx read/write.
-//   gate_dwg_partial / gate_dwg_reduce : dWg[m,e] = sum_t x[t,m] dl[t,e] as per-token-chunk
-//                  fp32 partial sums followed by a fixed-order fp64 reduction (no atomics, so
-//                  the result is the same on every run).  dbias[e] = sum_t dl[t,e] rides along
-//                  as an extra row m = M of the partials.
+//   E <= 16 : gate_bwd_fused (dlogits, dx and the dWg partial sums in one kernel) + gate_dwg_reduce.
+//   E  > 16 : gate_dlogits (one thread per token; norm_topk: dl[e_j] = w_j (dw_j - sum_j' w_j' dw_j'),
+//             otherwise dl[e] = sum_j dw_j p[e_j] (delta(e,e_j) - p[e]) with p = softmax(l)),
+//             gate_dx_wide (dx[t,m] (+)= sum_e dl[t,e] Wg[m,e]), gate_dwg_wide + gate_dwg_reduce.
+//   dWg[m,e] = sum_t x[t,m] dl[t,e] is formed as per-token-chunk fp32 partial sums followed by a
+//   fixed-order fp64 reduction (no atomics, so the result is the same on every run); dbias[e] =
+//   sum_t dl[t,e] rides along as an extra row m = M of the partials.
 #include "common.h"
 
 namespace {
 
 using namespace moe;
 
-constexpr int DX_TOK = 8;        // tokens per thread step in gate_dx
-constexpr int DX_TOK_BLK = 8;    // tokens per block in gate_dx
-// tokens per partial sum in gate_dwg_partial: a multiple of 8, at least 8, and at most 256 partial sums
-inline int dwg_chunk(int64_t S) { const int64_t c = (S + 255) / 256; return (int)(c < 8 ? 8 : (c + 7) / 8 * 8); }
+// tokens per dWg partial sum: a multiple of 8, at least 8, and at most 256 partial sums
+// (more than 16 experts: at most 64 partial sums of at least 64 tokens, the partials being E/8 times larger)
+inline int dwg_chunk(int64_t S, int E) {
+  const int64_t parts = E <= 16 ? 256 : 64, least = E <= 16 ? 8 : 64;
+  const int64_t c = (S + parts - 1) / parts;
+  return (int)(c < least ? least : (c + 7) / 8 * 8);
+}
 
 __global__ __launch_bounds__(256) void gate_dlogits(const float* __restrict__ dw, const float* __restrict__ w,
                                                     const int32_t* __restrict__ idx, const float* __restrict__ logits,
@@ -72,243 +73,6 @@ __device__ __forceinline__ void st8g(void* base, int64_t off, const float* f) {
     p[0] = make_float4(f[0], f[1], f[2], f[3]);
     p[1] = make_float4(f[4], f[5], f[6], f[7]);
   }
-}
-
-// grid: (ceil(M/8/128), ceil(S/DX_TOK_BLK)); block 128 threads, thread -> 8 consecutive m.
-// EC experts of Wg are held in registers at a time (EC = 8 when E <= 8, else 16); the old dx rows of
-// a step are requested before the FMAs so that their latency is covered.
-template <bool BF16, int EC>
-__global__ __launch_bounds__(128) void gate_dx(const float* __restrict__ dl, const float* __restrict__ Wg,
-                                               void* __restrict__ dx, int64_t S, int M, int E, int accumulate) {
-  const int m0 = (blockIdx.x * 128 + threadIdx.x) * 8;
-  if (m0 >= M) return;
-  const int64_t tb = (int64_t)blockIdx.y * DX_TOK_BLK;
-  for (int64_t t0 = tb; t0 < tb + DX_TOK_BLK && t0 < S; t0 += DX_TOK) {
-    float acc[DX_TOK][8];
-#pragma unroll
-    for (int i = 0; i < DX_TOK; ++i) {
-      if (accumulate && t0 + i < S) {
-        ld8g<BF16>(dx, (t0 + i) * (int64_t)M + m0, acc[i]);
-      } else {
-#pragma unroll
-        for (int q = 0; q < 8; ++q) acc[i][q] = 0.f;
-      }
-    }
-    for (int e0 = 0; e0 < E; e0 += EC) {
-      float wr[8][EC];
-#pragma unroll
-      for (int q = 0; q < 8; ++q)
-#pragma unroll
-        for (int e = 0; e < EC; ++e) wr[q][e] = (e0 + e < E) ? Wg[(int64_t)(m0 + q) * E + e0 + e] : 0.f;
-#pragma unroll
-      for (int i = 0; i < DX_TOK; ++i) {
-        const int64_t t = t0 + i;
-        if (t < S) {
-#pragma unroll
-          for (int e = 0; e < EC; ++e) {
-            const float d = (e0 + e < E) ? dl[t * E + e0 + e] : 0.f;
-#pragma unroll
-            for (int q = 0; q < 8; ++q) acc[i][q] = fmaf(d, wr[q][e], acc[i][q]);
-          }
-        }
-      }
-    }
-#pragma unroll
-    for (int i = 0; i < DX_TOK; ++i)
-      if (t0 + i < S) st8g<BF16>(dx, (t0 + i) * (int64_t)M + m0, acc[i]);
-  }
-}
-
-// grid: (ceil(M/8/128), nchunk); partial[chunk][m][e] for m < M, plus row m = M for dbias.
-template <bool BF16, int EC>
-__global__ __launch_bounds__(128) void gate_dwg_partial(const void* __restrict__ x, const float* __restrict__ dl,
-                                                        float* __restrict__ partial, int64_t S, int M, int E,
-                                                        int chunk) {
-  const int m0 = (blockIdx.x * 128 + threadIdx.x) * 8;
-  const int64_t tb = (int64_t)blockIdx.y * chunk;
-  const int64_t te = (tb + chunk < S) ? tb + chunk : S;
-  float* out = partial + (int64_t)blockIdx.y * (M + 1) * E;
-  if (m0 < M) {
-    for (int e0 = 0; e0 < E; e0 += EC) {
-      float acc[8][EC];
-#pragma unroll
-      for (int q = 0; q < 8; ++q)
-#pragma unroll
-        for (int e = 0; e < EC; ++e) acc[q][e] = 0.f;
-      int64_t t = tb;
-      for (; t + 4 <= te; t += 4) {       // four rows of x in flight
-        float xf[4][8];
-#pragma unroll
-        for (int u = 0; u < 4; ++u) ld8g<BF16>(x, (t + u) * (int64_t)M + m0, xf[u]);
-#pragma unroll
-        for (int u = 0; u < 4; ++u)
-#pragma unroll
-          for (int e = 0; e < EC; ++e) {
-            const float d = (e0 + e < E) ? dl[(t + u) * E + e0 + e] : 0.f;
-#pragma unroll
-            for (int q = 0; q < 8; ++q) acc[q][e] = fmaf(xf[u][q], d, acc[q][e]);
-          }
-      }
-      for (; t < te; ++t) {
-        float xf[8];
-        ld8g<BF16>(x, t * (int64_t)M + m0, xf);
-#pragma unroll
-        for (int e = 0; e < EC; ++e) {
-          const float d = (e0 + e < E) ? dl[t * E + e0 + e] : 0.f;
-#pragma unroll
-          for (int q = 0; q < 8; ++q) acc[q][e] = fmaf(xf[q], d, acc[q][e]);
-        }
-      }
-#pragma unroll
-      for (int q = 0; q < 8; ++q)
-#pragma unroll
-        for (int e = 0; e < EC; ++e)
-          if (e0 + e < E) out[(int64_t)(m0 + q) * E + e0 + e] = acc[q][e];
-    }
-  }
-  if (blockIdx.x == 0) {  // bias row: column sums of dl over this chunk
-    for (int e = threadIdx.x; e < E; e += 128) {
-      float s = 0.f;
-      for (int64_t t = tb; t < te; ++t) s += dl[t * E + e];
-      out[(int64_t)M * E + e] = s;
-    }
-  }
-}
-
-// ---- fast paths for E <= 16 (EC = 8 or 16 holds all experts): dl rows and the Wg tile go through
-// LDS with coalesced global accesses, zero-padded to EC, so the FMA loops have no conditions ----
-constexpr int GB_TOK = 32;                 // tokens per block
-constexpr int GB_MT = 1024;                // m per block (128 threads x 8)
-constexpr int GB_PITCH = GB_MT + 8;        // row pitch of the transposed Wg tile [e][m] in LDS (floats)
-
-// dx[t, m] (+)= sum_e dl[t,e] Wg[m,e]
-template <bool BF16, int EC>
-__global__ __launch_bounds__(128) void gate_dx_fast(const float* __restrict__ dl, const float* __restrict__ Wg,
-                                                    void* __restrict__ dx, int64_t S, int M, int E, int accumulate,
-                                                    int tok_blk /* <= GB_TOK, multiple of 8 */) {
-  constexpr int TS = EC <= 8 ? 8 : 4;   // tokens per step (register budget)
-  __shared__ __attribute__((aligned(16))) float wgs[EC * GB_PITCH];
-  __shared__ __attribute__((aligned(16))) float dls[GB_TOK * EC];
-  const int tid = threadIdx.x;
-  const int mb = blockIdx.x * GB_MT;
-  const int64_t tb = (int64_t)blockIdx.y * tok_blk;
-  for (int i = tid; i < GB_MT * EC; i += 128) {
-    const int m = i / EC, e = i - m * EC;
-    wgs[e * GB_PITCH + m] = (mb + m < M && e < E) ? Wg[(int64_t)(mb + m) * E + e] : 0.f;
-  }
-  for (int i = tid; i < tok_blk * EC; i += 128) {
-    const int t = i / EC, e = i - t * EC;
-    dls[i] = (tb + t < S && e < E) ? dl[(tb + t) * E + e] : 0.f;
-  }
-  __syncthreads();
-  const int ml = tid * 8, m0 = mb + ml;
-  if (m0 >= M) return;
-  float wr[EC][8];
-#pragma unroll
-  for (int e = 0; e < EC; ++e) {
-    const float4 a = *reinterpret_cast<const float4*>(&wgs[e * GB_PITCH + ml]);
-    const float4 b = *reinterpret_cast<const float4*>(&wgs[e * GB_PITCH + ml + 4]);
-    wr[e][0] = a.x; wr[e][1] = a.y; wr[e][2] = a.z; wr[e][3] = a.w;
-    wr[e][4] = b.x; wr[e][5] = b.y; wr[e][6] = b.z; wr[e][7] = b.w;
-  }
-#pragma unroll 1
-  for (int t0 = 0; t0 < tok_blk; t0 += TS) {
-    float acc[TS][8];
-#pragma unroll
-    for (int i = 0; i < TS; ++i) {
-      if (accumulate && tb + t0 + i < S) {
-        ld8g<BF16>(dx, (tb + t0 + i) * (int64_t)M + m0, acc[i]);
-      } else {
-#pragma unroll
-        for (int q = 0; q < 8; ++q) acc[i][q] = 0.f;
-      }
-    }
-#pragma unroll
-    for (int i = 0; i < TS; ++i) {
-#pragma unroll
-      for (int e4 = 0; e4 < EC; e4 += 4) {
-        const float4 d = *reinterpret_cast<const float4*>(&dls[(t0 + i) * EC + e4]);   // same address in all lanes
-        const float dv[4] = {d.x, d.y, d.z, d.w};
-#pragma unroll
-        for (int u = 0; u < 4; ++u)
-#pragma unroll
-          for (int q = 0; q < 8; ++q) acc[i][q] = fmaf(dv[u], wr[e4 + u][q], acc[i][q]);
-      }
-    }
-#pragma unroll
-    for (int i = 0; i < TS; ++i)
-      if (tb + t0 + i < S) st8g<BF16>(dx, (tb + t0 + i) * (int64_t)M + m0, acc[i]);
-  }
-}
-
-// partial[chunk][m][e] = sum over the chunk's tokens of x[t,m] dl[t,e]; the results leave through LDS
-// so that the [m][e] rows are written contiguously
-template <bool BF16, int EC>
-__global__ __launch_bounds__(128) void gate_dwg_partial_fast(const void* __restrict__ x, const float* __restrict__ dl,
-                                                             float* __restrict__ partial, int64_t S, int M, int E,
-                                                             int chunk) {
-  __shared__ __attribute__((aligned(16))) float outs[EC * GB_PITCH];
-  __shared__ __attribute__((aligned(16))) float dls[GB_TOK * EC];
-  const int tid = threadIdx.x;
-  const int mb = blockIdx.x * GB_MT;
-  const int ml = tid * 8, m0 = mb + ml;
-  const int64_t tb = (int64_t)blockIdx.y * chunk;
-  const int64_t te = (tb + chunk < S) ? tb + chunk : S;
-  float* out = partial + (int64_t)blockIdx.y * (M + 1) * E;
-  float acc[EC][8];
-#pragma unroll
-  for (int e = 0; e < EC; ++e)
-#pragma unroll
-    for (int q = 0; q < 8; ++q) acc[e][q] = 0.f;
-  float colsum = 0.f;   // thread e < E of block column 0 also sums dl[:, e] for the bias row
-  for (int64_t t0 = tb; t0 < te; t0 += GB_TOK) {
-    __syncthreads();
-    for (int i = tid; i < GB_TOK * EC; i += 128) {
-      const int t = i / EC, e = i - t * EC;
-      dls[i] = (t0 + t < te && e < E) ? dl[(t0 + t) * E + e] : 0.f;
-    }
-    __syncthreads();
-    if (blockIdx.x == 0 && tid < EC)
-      for (int t = 0; t < GB_TOK; ++t) colsum += dls[t * EC + tid];
-    if (m0 < M) {
-      const int nt = (int)((te - t0 < GB_TOK) ? te - t0 : GB_TOK);
-#pragma unroll 1
-      for (int ts = 0; ts < nt; ts += 4) {
-        float xf[4][8];
-#pragma unroll
-        for (int u = 0; u < 4; ++u) {
-          if (t0 + ts + u < te) {
-            ld8g<BF16>(x, (t0 + ts + u) * (int64_t)M + m0, xf[u]);
-          } else {
-#pragma unroll
-            for (int q = 0; q < 8; ++q) xf[u][q] = 0.f;
-          }
-        }
-#pragma unroll
-        for (int u = 0; u < 4; ++u)
-#pragma unroll
-          for (int e4 = 0; e4 < EC; e4 += 4) {
-            const float4 d = *reinterpret_cast<const float4*>(&dls[(ts + u) * EC + e4]);
-            const float dv[4] = {d.x, d.y, d.z, d.w};
-#pragma unroll
-            for (int v = 0; v < 4; ++v)
-#pragma unroll
-              for (int q = 0; q < 8; ++q) acc[e4 + v][q] = fmaf(xf[u][q], dv[v], acc[e4 + v][q]);
-          }
-      }
-    }
-  }
-#pragma unroll
-  for (int e = 0; e < EC; ++e) {
-    *reinterpret_cast<float4*>(&outs[e * GB_PITCH + ml]) = make_float4(acc[e][0], acc[e][1], acc[e][2], acc[e][3]);
-    *reinterpret_cast<float4*>(&outs[e * GB_PITCH + ml + 4]) = make_float4(acc[e][4], acc[e][5], acc[e][6], acc[e][7]);
-  }
-  __syncthreads();
-  for (int i = tid; i < GB_MT * EC; i += 128) {
-    const int m = i / EC, e = i - m * EC;
-    if (mb + m < M && e < E) out[(int64_t)(mb + m) * E + e] = outs[e * GB_PITCH + m];
-  }
-  if (blockIdx.x == 0 && tid < E && tid < EC) out[(int64_t)M * E + tid] = colsum;
 }
 
 // dWg[i] = sum over the chunks of partial[chunk][i], in a fixed order: the four waves of a block take
@@ -524,11 +288,138 @@ __global__ __launch_bounds__(NTHR) void gate_bwd_fused(const float* __restrict__
   if (blockIdx.x == 0 && tid < E && tid < EC) out[(int64_t)M * E + tid] = colsum;
 }
 
+// ---------------------------------------------------------------------------------------------
+// E > 16.  The two products are small-K / small-N GEMMs on the vector ALUs with everything shared
+// through LDS, experts taken 32 (dx) or 64 (dWg) at a time.
+//
+// gate_dx_wide: a block owns 64 tokens x 256 columns; thread = 4 columns x 16 tokens (64 fp32
+// accumulators that stay in registers across the expert chunks).  Per chunk the Wg slab goes to LDS
+// transposed, [e][column] with pitch 260, so a thread reads its 4 columns of an expert with one 16-byte
+// access and consecutive lanes are contiguous; dl rows are read as wave-wide broadcasts.
+// ---------------------------------------------------------------------------------------------
+constexpr int WX_EB = 32, WX_TOK = 64, WX_COLS = 256, WX_PITCH = WX_COLS + 4;
+template <bool BF16>
+__global__ __launch_bounds__(256) void gate_dx_wide(const float* __restrict__ dl, const float* __restrict__ Wg,
+                                                    void* __restrict__ dx, int64_t S, int M, int E, int accumulate) {
+  __shared__ __attribute__((aligned(16))) float wgs[WX_EB * WX_PITCH];
+  __shared__ __attribute__((aligned(16))) float dls[WX_TOK * WX_EB];
+  const int tid = threadIdx.x, cg = tid & 63, tg = tid >> 6;
+  const int cb = blockIdx.x * WX_COLS, c0 = cb + cg * 4;
+  const int64_t tb = (int64_t)blockIdx.y * WX_TOK, t0 = tb + tg * 16;
+  const bool cok = c0 < M;     // M is a multiple of 8, so 4 columns are in or out together
+  float acc[16][4];
+#pragma unroll
+  for (int t = 0; t < 16; ++t) {
+    if (accumulate && cok && t0 + t < S) {
+      ldn<BF16, 4>(dx, (t0 + t) * (int64_t)M + c0, acc[t]);
+    } else {
+#pragma unroll
+      for (int q = 0; q < 4; ++q) acc[t][q] = 0.f;
+    }
+  }
+  for (int ec = 0; ec < E; ec += WX_EB) {
+    __syncthreads();
+    for (int i = tid; i < WX_COLS * WX_EB; i += 256) {      // Wg[cb + c][ec + e], read along e
+      const int c = i / WX_EB, e = i - c * WX_EB;
+      wgs[e * WX_PITCH + c] = (cb + c < M && ec + e < E) ? Wg[(int64_t)(cb + c) * E + ec + e] : 0.f;
+    }
+    for (int i = tid; i < WX_TOK * WX_EB; i += 256) {
+      const int t = i / WX_EB, e = i - t * WX_EB;
+      dls[i] = (tb + t < S && ec + e < E) ? dl[(tb + t) * E + ec + e] : 0.f;
+    }
+    __syncthreads();
+#pragma unroll 2
+    for (int e4 = 0; e4 < WX_EB; e4 += 4) {
+      float4 wv[4];
+#pragma unroll
+      for (int j = 0; j < 4; ++j) wv[j] = *reinterpret_cast<const float4*>(&wgs[(e4 + j) * WX_PITCH + cg * 4]);
+#pragma unroll
+      for (int t = 0; t < 16; ++t) {
+        const float4 d = *reinterpret_cast<const float4*>(&dls[(tg * 16 + t) * WX_EB + e4]);
+        const float dv[4] = {d.x, d.y, d.z, d.w};
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          acc[t][0] = fmaf(dv[j], wv[j].x, acc[t][0]);
+          acc[t][1] = fmaf(dv[j], wv[j].y, acc[t][1]);
+          acc[t][2] = fmaf(dv[j], wv[j].z, acc[t][2]);
+          acc[t][3] = fmaf(dv[j], wv[j].w, acc[t][3]);
+        }
+      }
+    }
+  }
+  if (cok) {
+#pragma unroll
+    for (int t = 0; t < 16; ++t)
+      if (t0 + t < S) stn<BF16, 4>(dx, (t0 + t) * (int64_t)M + c0, acc[t]);
+  }
+}
+
+// gate_dwg_wide: a block owns one token chunk x 256 columns x 64 experts (grid.z walks the expert
+// blocks); thread = 4 columns x 16 experts (64 accumulators).  16 tokens at a time: their x pieces
+// are requested first, the dl rows staged in LDS and read as broadcasts (a wave shares its 16 experts).
+// partial[chunk][m][e] for m < M, plus row m = M (column sums of dl) for the bias gradient.
+template <bool BF16>
+__global__ __launch_bounds__(256) void gate_dwg_wide(const void* __restrict__ x, const float* __restrict__ dl,
+                                                     float* __restrict__ partial, int64_t S, int M, int E, int chunk) {
+  __shared__ __attribute__((aligned(16))) float dls[16 * 64];
+  const int tid = threadIdx.x, cg = tid & 63, eg = tid >> 6;
+  const int c0 = blockIdx.x * 256 + cg * 4;
+  const int eb = blockIdx.z * 64;
+  const bool cok = c0 < M;
+  const int64_t tb = (int64_t)blockIdx.y * chunk;
+  const int64_t te = (tb + chunk < S) ? tb + chunk : S;
+  float* out = partial + (int64_t)blockIdx.y * (M + 1) * E;
+  float acc[16][4];
+#pragma unroll
+  for (int j = 0; j < 16; ++j)
+#pragma unroll
+    for (int q = 0; q < 4; ++q) acc[j][q] = 0.f;
+  float colsum = 0.f;
+  for (int64_t t0 = tb; t0 < te; t0 += 16) {
+    RawRow<BF16, 4> xr[16];
+#pragma unroll
+    for (int u = 0; u < 16; ++u) {
+      if (cok && t0 + u < te) xr[u].load(x, (t0 + u) * (int64_t)M + c0); else xr[u].zero();
+    }
+    __syncthreads();
+    for (int i = tid; i < 16 * 64; i += 256) {
+      const int t = i >> 6, e = i & 63;
+      dls[i] = (t0 + t < te && eb + e < E) ? dl[(t0 + t) * E + eb + e] : 0.f;
+    }
+    __syncthreads();
+    if (blockIdx.x == 0 && tid < 64)
+      for (int t = 0; t < 16; ++t) colsum += dls[t * 64 + tid];
+#pragma unroll
+    for (int u = 0; u < 16; ++u) {
+      const float xv[4] = {xr[u].get(0), xr[u].get(1), xr[u].get(2), xr[u].get(3)};
+#pragma unroll
+      for (int j4 = 0; j4 < 16; j4 += 4) {
+        const float4 d = *reinterpret_cast<const float4*>(&dls[u * 64 + eg * 16 + j4]);
+        const float dv[4] = {d.x, d.y, d.z, d.w};
+#pragma unroll
+        for (int jj = 0; jj < 4; ++jj)
+#pragma unroll
+          for (int q = 0; q < 4; ++q) acc[j4 + jj][q] = fmaf(xv[q], dv[jj], acc[j4 + jj][q]);
+      }
+    }
+  }
+  if (cok) {
+#pragma unroll
+    for (int q = 0; q < 4; ++q)
+#pragma unroll
+      for (int j = 0; j < 16; ++j) {
+        const int e = eb + eg * 16 + j;
+        if (e < E) out[(int64_t)(c0 + q) * E + e] = acc[j][q];
+      }
+  }
+  if (blockIdx.x == 0 && tid < 64 && eb + tid < E) out[(int64_t)M * E + eb + tid] = colsum;
+}
+
 }  // namespace
 
 extern "C" size_t moe_gate_bwd_workspace_bytes(int64_t S, int M, int E) {
   if (S < 1 || M < 1 || E < 1) return 0;
-  const int chunk = dwg_chunk(S);
+  const int chunk = dwg_chunk(S, E);
   const int64_t nchunk = (S + chunk - 1) / chunk;
   return moe::align_up((size_t)nchunk * (size_t)(M + 1) * E * sizeof(float), 256);
 }
@@ -552,7 +443,7 @@ extern "C" int moe_gate_bwd(const float* dw, const float* w, const int32_t* idx,
   const bool bf = x_dtype == MOE_BF16;
   const int64_t n = (int64_t)(M + 1) * E;
   if (E <= 16) {   // one fused kernel, then the reduction of the partial sums
-    const int chunk = dwg_chunk(S);
+    const int chunk = dwg_chunk(S, E);
     const int nchunk = (int)((S + chunk - 1) / chunk);
     float* partial = (float*)ws;
     const int cols = E <= 8 ? 256 * 4 : 128 * 4;   // columns per block
@@ -568,29 +459,15 @@ extern "C" int moe_gate_bwd(const float* dw, const float* w, const int32_t* idx,
   }
   hipLaunchKernelGGL(gate_dlogits, dim3((unsigned)((S + 255) / 256)), dim3(256), 0, st, dw, w, idx, logits, S, E, k,
                      norm, dlogits);
-  const unsigned gm = (unsigned)((M / 8 + 127) / 128);
-  const dim3 grid_dx(gm, (unsigned)((S + DX_TOK_BLK - 1) / DX_TOK_BLK));
-#define MOE_GATE_BWD_LAUNCH(kern, grid, ...)                                                        \
-  do {                                                                                              \
-    if (bf) { if (E <= 8) hipLaunchKernelGGL((kern<true, 8>), grid, dim3(128), 0, st, __VA_ARGS__); \
-              else hipLaunchKernelGGL((kern<true, 16>), grid, dim3(128), 0, st, __VA_ARGS__); }     \
-    else { if (E <= 8) hipLaunchKernelGGL((kern<false, 8>), grid, dim3(128), 0, st, __VA_ARGS__);   \
-           else hipLaunchKernelGGL((kern<false, 16>), grid, dim3(128), 0, st, __VA_ARGS__); }       \
-  } while (0)
-  const int mblocks = (M + GB_MT - 1) / GB_MT;
-  const int tok_blk = ((int64_t)mblocks * ((S + GB_TOK - 1) / GB_TOK) >= 2048) ? GB_TOK : 8;   // keep the grid wide
-  const dim3 grid_fx((unsigned)mblocks, (unsigned)((S + tok_blk - 1) / tok_blk));
-  // the LDS-staged kernel pays off once there is enough work per staged Wg tile
-  if (E <= 16 && tok_blk == GB_TOK) MOE_GATE_BWD_LAUNCH(gate_dx_fast, grid_fx, dlogits, Wg, dx, S, M, E, dx_accumulate, tok_blk);
-  else MOE_GATE_BWD_LAUNCH(gate_dx, grid_dx, dlogits, Wg, dx, S, M, E, dx_accumulate);
-  const int chunk = dwg_chunk(S);
+  const dim3 grid_dx((unsigned)((M + WX_COLS - 1) / WX_COLS), (unsigned)((S + WX_TOK - 1) / WX_TOK));
+  if (bf) hipLaunchKernelGGL(gate_dx_wide<true>, grid_dx, dim3(256), 0, st, dlogits, Wg, dx, S, M, E, dx_accumulate);
+  else hipLaunchKernelGGL(gate_dx_wide<false>, grid_dx, dim3(256), 0, st, dlogits, Wg, dx, S, M, E, dx_accumulate);
+  const int chunk = dwg_chunk(S, E);
   const int nchunk = (int)((S + chunk - 1) / chunk);
-  const dim3 grid_p(gm, (unsigned)nchunk);
   float* partial = (float*)ws;
-  const dim3 grid_fp((unsigned)((M + GB_MT - 1) / GB_MT), (unsigned)nchunk);
-  if (E <= 16) MOE_GATE_BWD_LAUNCH(gate_dwg_partial_fast, grid_fp, x, dlogits, partial, S, M, E, chunk);
-  else MOE_GATE_BWD_LAUNCH(gate_dwg_partial, grid_p, x, dlogits, partial, S, M, E, chunk);
-#undef MOE_GATE_BWD_LAUNCH
+  const dim3 grid_w((unsigned)((M + 255) / 256), (unsigned)nchunk, (unsigned)((E + 63) / 64));
+  if (bf) hipLaunchKernelGGL(gate_dwg_wide<true>, grid_w, dim3(256), 0, st, x, dlogits, partial, S, M, E, chunk);
+  else hipLaunchKernelGGL(gate_dwg_wide<false>, grid_w, dim3(256), 0, st, x, dlogits, partial, S, M, E, chunk);
   hipLaunchKernelGGL(gate_dwg_reduce, dim3((unsigned)((n + 63) / 64)), dim3(256), 0, st, partial, nchunk, M, E, dWg,
                      dgate_bias);
   return moe::check_launch();
