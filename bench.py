@@ -147,6 +147,21 @@ def main():
         roofline.update({"bound": "alu", "peak": 78.6, "frac": round(achieved / 78.6, 5),
                          "kernel": "ffn_gemm_f32 (6 grouped GEMMs per step)"})
 
+    # Forward with the dispatch fused into the first GEMM (outside the timed region, every expert local):
+    # the pair of calls it replaces against the one call, events around 20 repetitions of each
+    fused = None
+    if L.closed:
+        def timed(fn, reps=20):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            fn(); torch.cuda.synchronize()
+            e0.record()
+            for _ in range(reps):
+                fn()
+            e1.record(); torch.cuda.synchronize()
+            return e0.elapsed_time(e1) / reps
+        fused = {"dispatch_plus_ffn_fwd_ms": round(timed(lambda: (L.dispatch(), L.ffn_fwd())), 4),
+                 "ffn_fwd_gather_ms": round(timed(L.ffn_fwd_gather), 4)}
+
     cpu = None
     if small and not args.no_cpu_baseline and L.closed:
         from oracle import moe_oracle as O
@@ -176,6 +191,7 @@ def main():
                                f"gate+dispatch+FFN+combine fwd+bwd"},
         "roofline": roofline, "cpu_baseline": cpu,
         "per_call_ms": {k: round(v, 4) for k, v in per_call.items()}, "per_call_steps": len(probed),
+        "fused_dispatch_fwd": fused,
     }
     print(json.dumps(out))
 

@@ -175,6 +175,24 @@ int moe_expert_ffn_fwd(const void* X, int dtype, const void* W1, const void* W2,
                        int n_src, int G, int64_t C, int M, int H, int esp_idx, int n_esp,
                        const int32_t* row_counts, void* Z, void* A, void* Y, void* stream);
 
+/* Forward with the dispatch fused into the first GEMM, for a rank that holds every expert
+ * (N_EP = N_ESP-sharded or not, no AlltoAll between gate and experts; Section III-B notes that
+ * the local duplication before the AlltoAll is virtual, and without an AlltoAll the [E,C,M]
+ * buffer itself need not exist): row c of expert e of the first GEMM is read straight from the
+ * token matrix through the gate's inverse slot map,
+ *   X[e, c, :] = x[inv[e, c] / k, :]   (inv[e, c] < 0: an empty slot, a zero row),
+ * which is exactly what moe_dispatch would have written, so Z, A and Y are the same values as
+ * moe_dispatch followed by moe_expert_ffn_fwd(n_src = 1, G = E) produces.
+ *   x    [S, M]      dtype, device, in (token rows)
+ *   inv  [E, C]      int32, device, in (from moe_gate_topk: t * k + j, or -1)
+ *   the other arguments as in moe_expert_ffn_fwd with n_src = 1, G = E.
+ * The backward call still takes the dispatched X (its weight gradient reduces over the slots),
+ * so this entry point serves forward-only use; S * k must be below 2^31.  Errors as above. */
+int moe_expert_ffn_fwd_gather(const void* x, int dtype, int64_t S, const int32_t* inv, int k,
+                              const void* W1, const void* W2, int E, int64_t C, int M, int H,
+                              int esp_idx, int n_esp, const int32_t* row_counts,
+                              void* Z, void* A, void* Y, void* stream);
+
 int moe_expert_ffn_bwd(const void* dY, const void* X, const void* Z, const void* A,
                        const void* W1, const void* W2, int dtype,
                        int n_src, int G, int64_t C, int M, int H, int esp_idx, int n_esp,

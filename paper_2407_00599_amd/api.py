@@ -64,6 +64,9 @@ def lib() -> ctypes.CDLL:
         L.moe_expert_ffn_fwd.restype = c_i
         L.moe_expert_ffn_fwd.argtypes = [c_p, c_i, c_p, c_p, c_i, c_i, c_i64, c_i, c_i, c_i, c_i,
                                          c_p, c_p, c_p, c_p, c_p]
+        L.moe_expert_ffn_fwd_gather.restype = c_i
+        L.moe_expert_ffn_fwd_gather.argtypes = [c_p, c_i, c_i64, c_p, c_i, c_p, c_p, c_i, c_i64, c_i, c_i, c_i, c_i,
+                                                c_p, c_p, c_p, c_p, c_p]
         L.moe_expert_ffn_bwd.restype = c_i
         L.moe_expert_ffn_bwd.argtypes = [c_p, c_p, c_p, c_p, c_p, c_p, c_i, c_i, c_i, c_i64, c_i, c_i, c_i, c_i,
                                          c_p, c_p, c_p, c_p, c_p, c_sz, c_p]
@@ -83,7 +86,7 @@ def lib() -> ctypes.CDLL:
 
 EXPORTED = [
     "moe_strerror", "moe_abi_version", "moe_capacity", "moe_gate_workspace_bytes", "moe_gate_topk",
-    "moe_dispatch", "moe_dispatch_slots", "moe_ffn_workspace_bytes", "moe_ffn_set_tile", "moe_ffn_executed_flops", "moe_expert_ffn_fwd", "moe_expert_ffn_bwd",
+    "moe_dispatch", "moe_dispatch_slots", "moe_ffn_workspace_bytes", "moe_ffn_set_tile", "moe_ffn_executed_flops", "moe_expert_ffn_fwd", "moe_expert_ffn_fwd_gather", "moe_expert_ffn_bwd",
     "moe_combine_fwd", "moe_combine_bwd", "moe_gate_bwd_workspace_bytes", "moe_gate_bwd", "moe_alpha_beta_fit",
     "moe_choose_schedule",
 ]
@@ -199,6 +202,12 @@ def moe_ffn_executed_flops(dtype, n_src, G, C, M, H, n_esp, row_counts_host=None
 def moe_expert_ffn_fwd(X, W1, W2, n_src, G, C, M, H, esp_idx, n_esp, Z, A, Y, row_counts=None):
     _check(lib().moe_expert_ffn_fwd(_ptr(X), dtype_code(X), _ptr(W1), _ptr(W2), n_src, G, C, M, H, esp_idx, n_esp,
                                     _ptr(row_counts), _ptr(Z), _ptr(A), _ptr(Y), _stream()), "moe_expert_ffn_fwd")
+
+
+def moe_expert_ffn_fwd_gather(x, inv, S, k, W1, W2, E, C, M, H, esp_idx, n_esp, Z, A, Y, row_counts=None):
+    _check(lib().moe_expert_ffn_fwd_gather(_ptr(x), dtype_code(x), S, _ptr(inv), k, _ptr(W1), _ptr(W2), E, C, M, H,
+                                           esp_idx, n_esp, _ptr(row_counts), _ptr(Z), _ptr(A), _ptr(Y), _stream()),
+           "moe_expert_ffn_fwd_gather")
 
 
 def moe_expert_ffn_bwd(dY, X, Z, A, W1, W2, n_src, G, C, M, H, esp_idx, n_esp, dX, dW1, dW2, ws, row_counts=None):

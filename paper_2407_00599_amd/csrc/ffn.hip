@@ -45,6 +45,11 @@ struct GemmArgs {
   void* C2;         // second output (the activation GeLU(Z)) for EPI_GELU
   const void* Zin;  // saved pre-activation for EPI_DGELU
   const int32_t* cnt;  // optional [n_src, G]: rows of chunk (s, g) at or beyond min(cnt, Cc) are zero padding
+  // fused dispatch (NN GEMMs, n_src = 1): A is the token matrix and row r of expert g is the token
+  // gather[g * Cc + r] / gather_k (the gate's inverse slot map; negative = empty slot, a zero row)
+  const int32_t* gather;
+  int gather_k;
+  int64_t gather_rows;  // rows of the token matrix
   int G, n_src;
   int Cc;           // rows per chunk (capacity C)
   int R;            // n_src * Cc: virtual rows per expert
@@ -60,6 +65,16 @@ struct GemmArgs {
 __device__ __forceinline__ int64_t phys_row(int r, int g, int G, int Cc) {
   const int s = r / Cc;
   return ((int64_t)s * G + g) * Cc + (r - s * Cc);
+}
+
+// Row of the A operand that virtual row r of expert g is read from: its place in the received layout,
+// or, with a gather map, the token that the slot holds (-1: an empty slot, read as zeros).
+__device__ __forceinline__ int64_t a_src_row(const GemmArgs& p, int r, int g) {
+  if (p.gather == nullptr) return phys_row(r, g, p.G, p.Cc);
+  const int iv = p.gather[(int64_t)g * p.Cc + r];
+  if (iv < 0) return -1;
+  const int64_t tok = iv / p.gather_k;
+  return tok < p.gather_rows ? tok : -1;   // an index past the token matrix is treated as an empty slot
 }
 
 // ------------------------------------------------------------------------------------------
@@ -295,7 +310,8 @@ __global__ __launch_bounds__(WM * WN * 64) void ffn_gemm_bf16(const GemmArgs p) 
 #pragma unroll
     for (int i = 0; i < SA::NCH; ++i) {
       const int r = m0 + (tid >> 3) + i * (NT / 8);
-      a_off[i] = (r < p.Mdim) ? (uint32_t)((phys_row(r, g, p.G, p.Cc) * p.lda + (tid & 7) * 8) * 2) : OOB;
+      const int64_t row = (r < p.Mdim) ? a_src_row(p, r, g) : -1;
+      a_off[i] = (row >= 0) ? (uint32_t)((row * p.lda + (tid & 7) * 8) * 2) : OOB;
     }
   }
   uint32_t b_off[B_TR ? 1 : SB::NCH];
@@ -751,7 +767,8 @@ __device__ __forceinline__ void gemm_dma_tile(const GemmArgs& p, char* smem, int
       const int rt = q * 16 + (lane >> 2);   // rows past a 192-row tile are never fetched
       const int r = m0 + rt;
       a_k[j] = kc_c * 8;
-      a_req[j] = (rt < TMR && r < p.Mdim) ? (uint32_t)((phys_row(r, g, p.G, p.Cc) * p.lda + kc_c * 8) * 2) : OOB;
+      const int64_t row = (rt < TMR && r < p.Mdim) ? a_src_row(p, r, g) : -1;
+      a_req[j] = (row >= 0) ? (uint32_t)((row * p.lda + kc_c * 8) * 2) : OOB;
     } else {
       const int k = 2 * q + (lane >> 5);
       const int col = m0 + (((lane & 31) ^ (4 * (k & 3))) * 8);
@@ -1020,7 +1037,10 @@ __global__ __launch_bounds__(256) void ffn_gemm_f32(const GemmArgs p) {
         float v = 0.f;
         if (m0 + i < p.Mdim && k0 + k < Kd) {
           if (KIND == KIND_TN) v = A[phys_row(k0 + k, g, p.G, p.Cc) * p.lda + m0 + i];
-          else v = A[phys_row(m0 + i, g, p.G, p.Cc) * p.lda + k0 + k];
+          else {
+            const int64_t row = a_src_row(p, m0 + i, g);
+            if (row >= 0) v = A[row * p.lda + k0 + k];
+          }
         }
         As[k][i] = v;
       }
@@ -1126,7 +1146,7 @@ TilePlan plan_tiles(bool tn, int G, int Mdim, int Ndim) {
 TilePlan prepare_bf16(GemmArgs& a, bool tn) {
   a.kchunks = (a.Cc + KT - 1) / KT;
   const uint64_t act_rows = (uint64_t)a.n_src * a.G * a.Cc;
-  a.a_bytes = act_rows * (uint64_t)a.lda * 2;
+  a.a_bytes = (a.gather ? (uint64_t)a.gather_rows : act_rows) * (uint64_t)a.lda * 2;
   a.b_bytes = tn ? act_rows * (uint64_t)a.ldb * 2 : (uint64_t)a.G * (uint64_t)a.b_goff * 2;
   const TilePlan t = plan_tiles(tn, a.G, a.Mdim, a.Ndim);
   a.tiles_n = (a.Ndim + t.tile_n - 1) / t.tile_n;
@@ -1229,9 +1249,9 @@ extern "C" size_t moe_ffn_workspace_bytes(int dtype, int n_src, int G, int64_t C
   return moe::align_up((size_t)n_src * G * C * (size_t)(H / n_esp) * esz, 256);   // dZ
 }
 
-extern "C" int moe_expert_ffn_fwd(const void* X, int dtype, const void* W1, const void* W2, int n_src, int G,
-                                  int64_t C, int M, int H, int esp_idx, int n_esp, const int32_t* row_counts, void* Z,
-                                  void* A, void* Y, void* stream) {
+static int ffn_fwd_impl(const void* X, const int32_t* gather, int gather_k, int64_t gather_rows, int dtype,
+                        const void* W1, const void* W2, int n_src, int G, int64_t C, int M, int H, int esp_idx,
+                        int n_esp, const int32_t* row_counts, void* Z, void* A, void* Y, void* stream) {
   if (int rc = check_ffn_shape(dtype, n_src, G, C, M, H, esp_idx, n_esp)) return rc;
   MOE_REQUIRE_PTR(X); MOE_REQUIRE_PTR(W1); MOE_REQUIRE_PTR(W2); MOE_REQUIRE_PTR(Z); MOE_REQUIRE_PTR(A);
   MOE_REQUIRE_PTR(Y);
@@ -1244,17 +1264,35 @@ extern "C" int moe_expert_ffn_fwd(const void* X, int dtype, const void* W1, cons
   a.G = G; a.n_src = n_src; a.Cc = (int)C; a.R = (int)(n_src * C); a.cnt = row_counts;
   // Z = X * W1[:, h0:h0+Hl] ; A = GeLU(Z)
   a.A = X; a.lda = M;
+  a.gather = gather; a.gather_k = gather_k; a.gather_rows = gather_rows;
   a.B = W1; a.ldb = H; a.b_goff = (int64_t)M * H; a.b_off = h0;
   a.C = Z; a.C2 = A; a.ldc = Hl;
   a.Mdim = a.R; a.Ndim = Hl; a.Kdim = M;
   launch_gemm<KIND_NN, EPI_GELU>(a, dtype, st);
   // Y = A * W2[h0:h0+Hl, :]
   a.A = A; a.lda = Hl;
+  a.gather = nullptr; a.gather_k = 0; a.gather_rows = 0;
   a.B = W2; a.ldb = M; a.b_goff = (int64_t)H * M; a.b_off = h0 * M;
   a.C = Y; a.C2 = nullptr; a.ldc = M;
   a.Mdim = a.R; a.Ndim = M; a.Kdim = Hl;
   launch_gemm<KIND_NN, EPI_STORE>(a, dtype, st);
   return moe::check_launch();
+}
+
+extern "C" int moe_expert_ffn_fwd(const void* X, int dtype, const void* W1, const void* W2, int n_src, int G,
+                                  int64_t C, int M, int H, int esp_idx, int n_esp, const int32_t* row_counts, void* Z,
+                                  void* A, void* Y, void* stream) {
+  return ffn_fwd_impl(X, nullptr, 0, 0, dtype, W1, W2, n_src, G, C, M, H, esp_idx, n_esp, row_counts, Z, A, Y, stream);
+}
+
+extern "C" int moe_expert_ffn_fwd_gather(const void* x, int dtype, int64_t S, const int32_t* inv, int k, const void* W1,
+                                         const void* W2, int E, int64_t C, int M, int H, int esp_idx, int n_esp,
+                                         const int32_t* row_counts, void* Z, void* A, void* Y, void* stream) {
+  MOE_REQUIRE(S >= 1 && k >= 1 && k <= MOE_MAX_K, MOE_EINVAL);
+  MOE_REQUIRE_PTR(inv);
+  MOE_REQUIRE((int64_t)S * k < (1ll << 31), MOE_EUNSUPPORTED);
+  if (dtype == MOE_BF16) MOE_REQUIRE((uint64_t)S * (uint64_t)M * 2 <= 0xFFFFFFF0ull, MOE_EUNSUPPORTED);
+  return ffn_fwd_impl(x, inv, k, S, dtype, W1, W2, 1, E, C, M, H, esp_idx, n_esp, row_counts, Z, A, Y, stream);
 }
 
 extern "C" int moe_expert_ffn_bwd(const void* dY, const void* X, const void* Z, const void* A, const void* W1,

@@ -60,6 +60,18 @@ class MoERankLayer:
         api.moe_combine_fwd(self.Yret, self.n_esp, S, M, E, k, C, self.idx, self.slot, self.w, self.y)
         return self.y
 
+    def forward_fused_dispatch(self, x_full, Wg, bias, W1, W2):
+        """Forward only, with the dispatch fused into the first GEMM (no [E, C, M] buffer is written);
+        backward() must not follow it, since the weight gradient reads the dispatched rows."""
+        S, M, E, k, C, H = self.S, self.M, self.E, self.k, self.C, self.H
+        self.x = x_full[self.mp_idx * S:(self.mp_idx + 1) * S]
+        self.gate(x_full, Wg, bias)
+        for j in range(self.n_esp):
+            api.moe_expert_ffn_fwd_gather(self.x, self.inv, S, k, W1, W2, E, C, M, H, j, self.n_esp, self.Z[j],
+                                          self.A[j], self.Yret[j], self.counts)
+        api.moe_combine_fwd(self.Yret, self.n_esp, S, M, E, k, C, self.idx, self.slot, self.w, self.y)
+        return self.y
+
     def backward(self, dy):
         S, M, E, k, C, H = self.S, self.M, self.E, self.k, self.C, self.H
         api.moe_combine_bwd(dy, self.Yret, self.n_esp, S, M, E, k, C, self.idx, self.slot, self.inv, self.w,
@@ -218,6 +230,12 @@ class MoERankShape:
     def ffn_fwd(self):
         api.moe_expert_ffn_fwd(self.Xrecv, self.W1, self.W2, self.n_src, self.G, self.C, self.M, self.H, self.esp_idx,
                                self.n_esp, self.Z, self.A, self.Yout, self.row_counts)
+
+    def ffn_fwd_gather(self):
+        """dispatch + ffn_fwd in one call (every expert local); not one of STEPS."""
+        assert self.closed
+        api.moe_expert_ffn_fwd_gather(self.x, self.inv, self.S, self.k, self.W1, self.W2, self.E, self.C, self.M,
+                                      self.H, self.esp_idx, self.n_esp, self.Z, self.A, self.Yout, self.row_counts)
 
     def combine(self):
         api.moe_combine_fwd(self.Yret, self.n_esp, self.S, self.M, self.E, self.k, self.C, self.idx, self.slot,

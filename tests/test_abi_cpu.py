@@ -35,7 +35,7 @@ def test_every_declared_symbol_is_exported_and_bound(L):
     for n in names:                       # the Python binding has the same names
         if n not in ("moe_strerror", "moe_abi_version"):
             assert hasattr(api, n), n
-    assert L.moe_abi_version() == 3
+    assert L.moe_abi_version() == 4
 
 
 def test_error_strings(L):
@@ -120,6 +120,13 @@ def test_ffn_argument_checks(L):
     assert fwd(X=None) == -6
     assert fwd(Z=U) == -3
     assert fwd(Act=None) == -6
+    def fwd_g(x=A, S=16, inv=A, k=2, E=2, C=10, M=64, H=128, Z=A):
+        return L.moe_expert_ffn_fwd_gather(x, 1, S, inv, k, A, A, E, C, M, H, 0, 1, None, Z, A, A, None)
+    assert fwd_g(k=0) == -1 and fwd_g(k=9) == -1 and fwd_g(S=0) == -1
+    assert fwd_g(inv=None) == -6 and fwd_g(x=None) == -6
+    assert fwd_g(inv=U) == -3
+    assert fwd_g(S=1 << 30, k=2) == -2             # S * k must stay below 2^31
+    assert fwd_g(M=60) == -2
     assert L.moe_expert_ffn_bwd(A, A, A, A, A, A, 1, 1, 2, 10, 64, 128, 0, 1, None, A, A, None, A, 1 << 30, None) == -6
     assert L.moe_expert_ffn_bwd(A, A, A, None, A, A, 1, 1, 2, 10, 64, 128, 0, 1, None, A, A, A, A, 1 << 30, None) == -6
     assert L.moe_expert_ffn_bwd(A, A, A, A, A, A, 1, 1, 2, 10, 64, 128, 0, 1, None, A, A, A, A, 64, None) == -5

@@ -76,3 +76,20 @@ def test_two_runs_are_bit_identical():
     torch.cuda.synchronize()
     for n, t in first.items():
         assert torch.equal(getattr(L, n), t), n
+
+
+@pytest.mark.parametrize("name,n_esp", [("tiny_fp32", 2), ("layer_bf16", 1), ("mp4_ep", 2)])
+def test_forward_with_fused_dispatch_is_the_same_forward(name, n_esp):
+    """Real routing from the gate: the forward that reads token rows through the inverse slot map gives the
+    bits of the forward that dispatches first, and matches the checker."""
+    cfg = synth.CONFIGS[name]
+    L, r, g, args, _ = run_layer(cfg, n_esp, 1)
+    ref = {n: getattr(L, n).clone() for n in ("Z", "A", "Yret", "y")}
+    for n in ref:
+        getattr(L, n).fill_(5.0)
+    L.buf.fill_(float("nan"))                  # the fused path must not read the dispatch buffer
+    L.forward_fused_dispatch(*args)
+    torch.cuda.synchronize()
+    for n, t in ref.items():
+        assert torch.equal(getattr(L, n), t), n
+    assert rel_err(to_host(L.y), r["y"]) <= TOL[cfg.dtype]
