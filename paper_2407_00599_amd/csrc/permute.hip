@@ -130,6 +130,86 @@ __global__ __launch_bounds__(256) void combine_rows(const void* __restrict__ Yre
   }
 }
 
+// The common case (k <= 2 choices per token, 1, 2 or 4 partial sums per slot) with K and P fixed at
+// compile time: all K * P * NCH row pieces of a step are requested before the first is used, NCH
+// 512-element chunks per step so that about eight 16-byte loads per lane are in flight.
+template <bool BF16>
+struct Piece {   // 8 consecutive elements as loaded
+  uint4 a, b;    // bf16: a only
+};
+// loaded with the non-temporal hint: each returned row is read exactly once (measured: 266 -> 234 us for
+// 1.3 GB at S = 32768, M = 4096; the same hint on the store of y costs 4 %)
+template <bool BF16>
+__device__ __forceinline__ void ld_piece(Piece<BF16>& r, const void* base, int64_t off) {
+  typedef unsigned int u32x4_t __attribute__((ext_vector_type(4)));
+  if (BF16) {
+    const u32x4_t v = __builtin_nontemporal_load(reinterpret_cast<const u32x4_t*>(reinterpret_cast<const bf16_t*>(base) + off));
+    r.a = make_uint4(v.x, v.y, v.z, v.w);
+  } else {
+    const u32x4_t* p = reinterpret_cast<const u32x4_t*>(reinterpret_cast<const float*>(base) + off);
+    const u32x4_t v0 = __builtin_nontemporal_load(p), v1 = __builtin_nontemporal_load(p + 1);
+    r.a = make_uint4(v0.x, v0.y, v0.z, v0.w); r.b = make_uint4(v1.x, v1.y, v1.z, v1.w);
+  }
+}
+template <bool BF16>
+__device__ __forceinline__ void piece_to_f32(const Piece<BF16>& r, float* f) {
+  if (BF16) unpack_bf16x8(r.a, f);
+  else {
+    f[0] = __uint_as_float(r.a.x); f[1] = __uint_as_float(r.a.y); f[2] = __uint_as_float(r.a.z); f[3] = __uint_as_float(r.a.w);
+    f[4] = __uint_as_float(r.b.x); f[5] = __uint_as_float(r.b.y); f[6] = __uint_as_float(r.b.z); f[7] = __uint_as_float(r.b.w);
+  }
+}
+template <bool BF16, int K, int P>
+__global__ __launch_bounds__(256) void combine_rows_kp(const void* __restrict__ Yret, const int32_t* __restrict__ idx,
+                                                       const int32_t* __restrict__ slot, const float* __restrict__ w,
+                                                       void* __restrict__ y, int64_t S, int M, int64_t C,
+                                                       int64_t part_stride) {
+  constexpr int NCH = (K * P >= 8) ? 1 : (K * P >= 4) ? 2 : 4;
+  const int lane = threadIdx.x & 63;
+  const int64_t t = (int64_t)blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6);
+  if (t >= S) return;
+  int64_t src[K];
+  float wt[K];
+#pragma unroll
+  for (int j = 0; j < K; ++j) {
+    const int c = slot[t * K + j];
+    src[j] = c >= 0 ? ((int64_t)idx[t * K + j] * C + c) * M : -1;
+    wt[j] = (c >= 0) ? (w ? w[t * K + j] : 1.f) : 0.f;
+  }
+  for (int m0 = lane * 8; m0 < M; m0 += 512 * NCH) {
+    Piece<BF16> raw[NCH][K][P];
+#pragma unroll
+    for (int c = 0; c < NCH; ++c)
+#pragma unroll
+      for (int j = 0; j < K; ++j)
+        if (src[j] >= 0 && m0 + 512 * c < M) {
+#pragma unroll
+          for (int p = 0; p < P; ++p) ld_piece<BF16>(raw[c][j][p], Yret, src[j] + p * part_stride + m0 + 512 * c);
+        }
+#pragma unroll
+    for (int c = 0; c < NCH; ++c) {
+      if (m0 + 512 * c >= M) break;
+      float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+      for (int j = 0; j < K; ++j)
+        if (src[j] >= 0) {
+          float r[8];
+          piece_to_f32<BF16>(raw[c][j][0], r);
+#pragma unroll
+          for (int p = 1; p < P; ++p) {
+            float q[8];
+            piece_to_f32<BF16>(raw[c][j][p], q);
+#pragma unroll
+            for (int i = 0; i < 8; ++i) r[i] += q[i];
+          }
+#pragma unroll
+          for (int i = 0; i < 8; ++i) acc[i] = fmaf(wt[j], r[i], acc[i]);
+        }
+      st8<BF16>(y, t * (int64_t)M + m0 + 512 * c, acc);
+    }
+  }
+}
+
 // dw[t,j] = <dy[t,:], sum_p Yret[p, idx, slot, :]>, 0 for dropped choices.  One wave per token.
 template <bool BF16>
 __global__ __launch_bounds__(256) void combine_dw(const void* __restrict__ dy, const void* __restrict__ Yret,
@@ -180,6 +260,67 @@ __global__ __launch_bounds__(256) void combine_dw(const void* __restrict__ dy, c
   }
 }
 
+template <bool BF16, int K, int P>
+__global__ __launch_bounds__(256) void combine_dw_kp(const void* __restrict__ dy, const void* __restrict__ Yret,
+                                                     const int32_t* __restrict__ idx, const int32_t* __restrict__ slot,
+                                                     float* __restrict__ dw, int64_t S, int M, int64_t C,
+                                                     int64_t part_stride) {
+  constexpr int NCH = (K * P >= 8) ? 1 : (K * P >= 4) ? 2 : 4;
+  const int lane = threadIdx.x & 63;
+  const int64_t t = (int64_t)blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6);
+  if (t >= S) return;
+  int64_t src[K];
+  float dot[K];
+#pragma unroll
+  for (int j = 0; j < K; ++j) {
+    const int c = slot[t * K + j];
+    src[j] = c >= 0 ? ((int64_t)idx[t * K + j] * C + c) * M : -1;
+    dot[j] = 0.f;
+  }
+  for (int m0 = lane * 8; m0 < M; m0 += 512 * NCH) {
+    Piece<BF16> raw[NCH][K][P], gr[NCH];
+#pragma unroll
+    for (int c = 0; c < NCH; ++c)
+      if (m0 + 512 * c < M) {
+        ld_piece<BF16>(gr[c], dy, t * (int64_t)M + m0 + 512 * c);
+#pragma unroll
+        for (int j = 0; j < K; ++j)
+          if (src[j] >= 0) {
+#pragma unroll
+            for (int p = 0; p < P; ++p) ld_piece<BF16>(raw[c][j][p], Yret, src[j] + p * part_stride + m0 + 512 * c);
+          }
+      }
+#pragma unroll
+    for (int c = 0; c < NCH; ++c) {
+      if (m0 + 512 * c >= M) break;
+      float g[8];
+      piece_to_f32<BF16>(gr[c], g);
+#pragma unroll
+      for (int j = 0; j < K; ++j)
+        if (src[j] >= 0) {
+          float r[8];
+          piece_to_f32<BF16>(raw[c][j][0], r);
+#pragma unroll
+          for (int p = 1; p < P; ++p) {
+            float q[8];
+            piece_to_f32<BF16>(raw[c][j][p], q);
+#pragma unroll
+            for (int i = 0; i < 8; ++i) r[i] += q[i];
+          }
+#pragma unroll
+          for (int i = 0; i < 8; ++i) dot[j] = fmaf(g[i], r[i], dot[j]);
+        }
+    }
+  }
+#pragma unroll
+  for (int j = 0; j < K; ++j) {
+    float d = dot[j];
+#pragma unroll
+    for (int o = 32; o >= 1; o >>= 1) d += __shfl_xor(d, o, 64);
+    if (lane == 0) dw[t * K + j] = d;
+  }
+}
+
 }  // namespace
 
 extern "C" int moe_dispatch_slots(const void* x, int dtype, int64_t S, int M, int E, int k, int64_t C, int64_t c0,
@@ -214,10 +355,17 @@ extern "C" int moe_combine_fwd(const void* Yret, int dtype, int n_part, int64_t 
   const dim3 grid((unsigned)((S + 3) / 4)), block(256);
   const int64_t ps = (int64_t)E * C * M;
   hipStream_t st = (hipStream_t)stream;
-  if (dtype == MOE_BF16)
-    hipLaunchKernelGGL(combine_rows<true>, grid, block, 0, st, Yret, idx, slot, w, y, S, M, k, C, n_part, ps);
-  else
-    hipLaunchKernelGGL(combine_rows<false>, grid, block, 0, st, Yret, idx, slot, w, y, S, M, k, C, n_part, ps);
+  const bool bf = dtype == MOE_BF16;
+#define COMBINE_KP(K_, P_)                                                                                          \
+  if (k == K_ && n_part == P_) {                                                                                    \
+    if (bf) hipLaunchKernelGGL((combine_rows_kp<true, K_, P_>), grid, block, 0, st, Yret, idx, slot, w, y, S, M, C, ps); \
+    else hipLaunchKernelGGL((combine_rows_kp<false, K_, P_>), grid, block, 0, st, Yret, idx, slot, w, y, S, M, C, ps);   \
+    return moe::check_launch();                                                                                     \
+  }
+  COMBINE_KP(1, 1) COMBINE_KP(1, 2) COMBINE_KP(1, 4) COMBINE_KP(2, 1) COMBINE_KP(2, 2) COMBINE_KP(2, 4)
+#undef COMBINE_KP
+  if (bf) hipLaunchKernelGGL(combine_rows<true>, grid, block, 0, st, Yret, idx, slot, w, y, S, M, k, C, n_part, ps);
+  else hipLaunchKernelGGL(combine_rows<false>, grid, block, 0, st, Yret, idx, slot, w, y, S, M, k, C, n_part, ps);
   return moe::check_launch();
 }
 
@@ -233,12 +381,20 @@ extern "C" int moe_combine_bwd(const void* dy, const void* Yret, int dtype, int 
   const int64_t rows = (int64_t)E * C;
   const int64_t ps = rows * M;
   const dim3 block(256), grid_r((unsigned)((rows + 3) / 4)), grid_t((unsigned)((S + 3) / 4));
-  if (dtype == MOE_BF16) {
-    if (dYret) hipLaunchKernelGGL(dispatch_rows<true>, grid_r, block, 0, st, dy, inv, w, dYret, rows, M, k, C, (int64_t)0, C);
-    hipLaunchKernelGGL(combine_dw<true>, grid_t, block, 0, st, dy, Yret, idx, slot, dw, S, M, k, C, n_part, ps);
-  } else {
-    if (dYret) hipLaunchKernelGGL(dispatch_rows<false>, grid_r, block, 0, st, dy, inv, w, dYret, rows, M, k, C, (int64_t)0, C);
-    hipLaunchKernelGGL(combine_dw<false>, grid_t, block, 0, st, dy, Yret, idx, slot, dw, S, M, k, C, n_part, ps);
+  const bool bf = dtype == MOE_BF16;
+  if (dYret) {
+    if (bf) hipLaunchKernelGGL(dispatch_rows<true>, grid_r, block, 0, st, dy, inv, w, dYret, rows, M, k, C, (int64_t)0, C);
+    else hipLaunchKernelGGL(dispatch_rows<false>, grid_r, block, 0, st, dy, inv, w, dYret, rows, M, k, C, (int64_t)0, C);
   }
+#define COMBINE_DW_KP(K_, P_)                                                                                          \
+  if (k == K_ && n_part == P_) {                                                                                       \
+    if (bf) hipLaunchKernelGGL((combine_dw_kp<true, K_, P_>), grid_t, block, 0, st, dy, Yret, idx, slot, dw, S, M, C, ps); \
+    else hipLaunchKernelGGL((combine_dw_kp<false, K_, P_>), grid_t, block, 0, st, dy, Yret, idx, slot, dw, S, M, C, ps);   \
+    return moe::check_launch();                                                                                        \
+  }
+  COMBINE_DW_KP(1, 1) COMBINE_DW_KP(1, 2) COMBINE_DW_KP(1, 4) COMBINE_DW_KP(2, 1) COMBINE_DW_KP(2, 2) COMBINE_DW_KP(2, 4)
+#undef COMBINE_DW_KP
+  if (bf) hipLaunchKernelGGL(combine_dw<true>, grid_t, block, 0, st, dy, Yret, idx, slot, dw, S, M, k, C, n_part, ps);
+  else hipLaunchKernelGGL(combine_dw<false>, grid_t, block, 0, st, dy, Yret, idx, slot, dw, S, M, k, C, n_part, ps);
   return moe::check_launch();
 }
