@@ -144,8 +144,9 @@ __device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void* base, ui
 __device__ __forceinline__ void pin(uint4& v) {
   asm volatile("" : "+v"(v.x), "+v"(v.y), "+v"(v.z), "+v"(v.w));
 }
+template <bool STREAM = false>   // STREAM: non-temporal hint, for data read here for the last time
 __device__ __forceinline__ uint4 ldb16(__amdgpu_buffer_rsrc_t r, uint32_t byte_off) {
-  const u32x4_t v = __builtin_amdgcn_raw_buffer_load_b128(r, (int)byte_off, 0, 0);
+  const u32x4_t v = __builtin_amdgcn_raw_buffer_load_b128(r, (int)byte_off, 0, STREAM ? 2 : 0);
   return make_uint4(v.x, v.y, v.z, v.w);
 }
 
@@ -538,9 +539,13 @@ __global__ __launch_bounds__(WM * WN * 64) void ffn_gemm_bf16(const GemmArgs p) 
 // same way.  Global memory is addressed through buffer descriptors with 32-bit byte offsets, so
 // the code is branch-free: a row or column outside the problem gets an out-of-range offset, which
 // the hardware drops (stores) or answers with zeros (loads).
+// STREAM = the non-temporal hint, for tensors that are not read again soon (the saved pre-activation,
+// the weight gradients): they then do not push the weights and the live activations out of the
+// last-level cache, which the next GEMMs read their operands from.
+template <bool STREAM = false>
 __device__ __forceinline__ void stb16(__amdgpu_buffer_rsrc_t r, uint32_t byte_off, const uint4& v) {
   const u32x4_t q = {v.x, v.y, v.z, v.w};
-  __builtin_amdgcn_raw_buffer_store_b128(q, r, (int)byte_off, 0, 0);
+  __builtin_amdgcn_raw_buffer_store_b128(q, r, (int)byte_off, 0, STREAM ? 2 : 0);
 }
 template <int KIND, int EPI, int MB, int NBK>
 __device__ __forceinline__ void store_tile_lds(const GemmArgs& p, f32x16_t (&acc)[MB][NBK], char* wave_lds, int g,
@@ -627,7 +632,7 @@ __device__ __forceinline__ void store_tile_lds(const GemmArgs& p, f32x16_t (&acc
     if (EPI == EPI_DGELU) {  // bring in the saved pre-activation, row-wise
 #pragma unroll
       for (int t = 0; t < NT_; ++t)
-        *reinterpret_cast<uint4*>(buf0 + (RPI * t + rl) * PITCH_B + cc * 16) = ldb16(rZ, off[i][t]);
+        *reinterpret_cast<uint4*>(buf0 + (RPI * t + rl) * PITCH_B + cc * 16) = ldb16<true>(rZ, off[i][t]);
     }
 #pragma unroll
     for (int j = 0; j < NBK; ++j) {
@@ -658,7 +663,8 @@ __device__ __forceinline__ void store_tile_lds(const GemmArgs& p, f32x16_t (&acc
     // row-wise read-back and store (LDS operations of one wave complete in program order)
 #pragma unroll
     for (int t = 0; t < NT_; ++t) {
-      stb16(rC, off[i][t], *reinterpret_cast<const uint4*>(buf0 + (RPI * t + rl) * PITCH_B + cc * 16));
+      stb16<(EPI == EPI_GELU || KIND == KIND_TN)>(rC, off[i][t],
+                                                   *reinterpret_cast<const uint4*>(buf0 + (RPI * t + rl) * PITCH_B + cc * 16));
       if (EPI == EPI_GELU)
         stb16(rC2, off[i][t], *reinterpret_cast<const uint4*>(buf1 + (RPI * t + rl) * PITCH_B + cc * 16));
     }
