@@ -576,32 +576,36 @@ __device__ __forceinline__ void store_tile_lds(const GemmArgs& p, f32x16_t (&acc
     rC2 = make_rsrc(EPI == EPI_GELU ? p.C2 : p.C, bytes);
     rZ = make_rsrc(EPI == EPI_DGELU ? p.Zin : p.C, bytes);
   }
-  // byte offset of (row, ncol) for the rows this lane touches in the row-wise phase, or OOB
+  // byte offset of (row, ncol) for the rows this lane touches in the row-wise phase, or OOB.  One
+  // multiplication per lane; the rows of a wave tile are then a constant number of leading dimensions apart.
   uint32_t off[MB][NT_];
+  const uint32_t ldc2 = (uint32_t)p.ldc * 2u;
   if (KIND == KIND_TN) {
+    const uint32_t base = ((uint32_t)(mbase + rl) * (uint32_t)p.ldc + (uint32_t)ncol) * 2u;
 #pragma unroll
     for (int i = 0; i < MB; ++i)
 #pragma unroll
       for (int t = 0; t < NT_; ++t) {
-        const int m = mbase + i * 32 + RPI * t + rl;
-        off[i][t] = (m < p.Mdim && col_ok) ? ((uint32_t)m * (uint32_t)p.ldc + (uint32_t)ncol) * 2u : OOB;
+        const int d = i * 32 + RPI * t;
+        off[i][t] = (mbase + d + rl < p.Mdim && col_ok) ? base + (uint32_t)d * ldc2 : OOB;
       }
   } else {
     // virtual row r of expert g is physical row ((r / C) G + g) C + r % C; one division for the
-    // wave tile, then a compare per row (a wave tile crosses at most one chunk boundary if C is not
-    // smaller than its height)
+    // wave tile (a wave tile crosses at most one chunk boundary if C is not smaller than its
+    // height: rows past it lie (G - 1) C physical rows further on)
     const int q0 = mbase / p.Cc, r0 = mbase - q0 * p.Cc;
     if (p.Cc >= 32 * MB) {
+      const uint32_t row0 = (uint32_t)((q0 * p.G + g) * p.Cc + r0 + rl);
+      const uint32_t base = (row0 * (uint32_t)p.ldc + (uint32_t)ncol) * 2u;
+      const uint32_t wrap_add = (uint32_t)(p.G - 1) * (uint32_t)p.Cc * ldc2;
+      const int to_wrap = p.Cc - r0 - rl;     // rows at or beyond this distance are in the next chunk
 #pragma unroll
       for (int i = 0; i < MB; ++i)
 #pragma unroll
         for (int t = 0; t < NT_; ++t) {
-          const int d = i * 32 + RPI * t + rl;
-          int rr = r0 + d;
-          const bool wrap = rr >= p.Cc;
-          rr -= wrap ? p.Cc : 0;
-          const uint32_t row = (uint32_t)(((q0 + (wrap ? 1 : 0)) * p.G + g) * p.Cc + rr);
-          off[i][t] = (mbase + d < p.Mdim && col_ok) ? (row * (uint32_t)p.ldc + (uint32_t)ncol) * 2u : OOB;
+          const int d = i * 32 + RPI * t;
+          const uint32_t o = base + (uint32_t)d * ldc2 + (d >= to_wrap ? wrap_add : 0u);
+          off[i][t] = (mbase + d + rl < p.Mdim && col_ok) ? o : OOB;
         }
     } else {
 #pragma unroll
