@@ -382,13 +382,60 @@ __global__ __launch_bounds__(256) void gate_scan(const int32_t* __restrict__ blo
   if (lane == 0) counts[e] = run;
 }
 
+// SCAN = false: queue positions of the block's first tokens come from gate_scan (blockbase, counts).
+// SCAN = true (few token blocks): every block works them out itself from the per-block histograms --
+// for each (choice j, expert e) the demand of the earlier blocks, plus all demand of the earlier
+// choices -- which saves the scan launch; block 0 also writes counts.  Same integers either way.
+template <bool SCAN>
 __global__ __launch_bounds__(GATE_TB) void gate_slots(const int32_t* __restrict__ idx, const int32_t* __restrict__ blockbase,
-                                                       const int32_t* __restrict__ counts, int64_t S, int E, int k,
+                                                       int32_t* __restrict__ counts, int64_t S, int E, int k,
                                                        int64_t C, int32_t* __restrict__ slot, int32_t* __restrict__ inv) {
+  static_assert(GATE_TB == 64, "one wave per block");
   __shared__ int wavecnt[GATE_TB / 64][MOE_MAX_E];
+  __shared__ int base_s[SCAN ? MOE_MAX_K * MOE_MAX_E : 1];   // queue position of this block's first (j, e) token
+  __shared__ int tot_s[SCAN ? MOE_MAX_K * MOE_MAX_E : 1];    // demand of (j, e) over all blocks
+  __shared__ int count_s[SCAN ? MOE_MAX_E : 1];              // total demand of expert e
   const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
   const int64_t t = (int64_t)blockIdx.x * GATE_TB + tid;
   const bool live = t < S;
+  if (SCAN) {
+    // here blockbase holds the histograms [j][e][b].  Lanes run over b; sixteen (j, e) rows at a time, so that
+    // sixteen loads are in flight per lane; the wave-wide sums of a row: its total and the part of the
+    // blocks before this one.
+    const int nblk = (int)gridDim.x, me = (int)blockIdx.x, npair = k * E;
+    for (int p0 = 0; p0 < npair; p0 += 16) {
+      int tot[16], pre[16];
+#pragma unroll
+      for (int u = 0; u < 16; ++u) tot[u] = pre[u] = 0;
+      for (int b0 = 0; b0 < nblk; b0 += 64) {
+        const int b = b0 + lane;
+        int h[16];
+#pragma unroll
+        for (int u = 0; u < 16; ++u) h[u] = (b < nblk && p0 + u < npair) ? blockbase[(int64_t)(p0 + u) * nblk + b] : 0;
+#pragma unroll
+        for (int u = 0; u < 16; ++u) { tot[u] += h[u]; pre[u] += b < me ? h[u] : 0; }
+      }
+#pragma unroll
+      for (int u = 0; u < 16; ++u) {
+#pragma unroll
+        for (int o = 32; o >= 1; o >>= 1) { tot[u] += __shfl_xor(tot[u], o, 64); pre[u] += __shfl_xor(pre[u], o, 64); }
+        if (lane == 0 && p0 + u < npair) { base_s[p0 + u] = pre[u]; tot_s[p0 + u] = tot[u]; }
+      }
+    }
+    __syncthreads();
+    // choice-major queues: all demand of the earlier choices at expert e comes first
+    for (int e = tid; e < E; e += GATE_TB) {
+      int run = 0;
+      for (int j = 0; j < k; ++j) {
+        const int i = j * E + e;
+        base_s[i] += run;
+        run += tot_s[i];
+      }
+      count_s[e] = run;
+      if (me == 0) counts[e] = run;
+    }
+    __syncthreads();
+  }
   for (int j = 0; j < k; ++j) {
     for (int i = tid; i < (GATE_TB / 64) * MOE_MAX_E; i += GATE_TB) (&wavecnt[0][0])[i] = 0;
     __syncthreads();
@@ -407,7 +454,7 @@ __global__ __launch_bounds__(GATE_TB) void gate_slots(const int32_t* __restrict_
     }
     __syncthreads();
     if (live) {
-      int pos = blockbase[((int64_t)j * E + e) * gridDim.x + blockIdx.x] + rank;
+      int pos = (SCAN ? base_s[j * E + e] : blockbase[((int64_t)j * E + e) * gridDim.x + blockIdx.x]) + rank;
       for (int q = 0; q < wv; ++q) pos += wavecnt[q][e];
       const bool keep = pos < C;
       slot[t * k + j] = keep ? pos : -1;
@@ -420,7 +467,7 @@ __global__ __launch_bounds__(GATE_TB) void gate_slots(const int32_t* __restrict_
   for (int64_t i = (int64_t)blockIdx.x * GATE_TB + tid; i < total; i += (int64_t)gridDim.x * GATE_TB) {
     const int e = (int)(i / C);
     const int64_t c = i - (int64_t)e * C;
-    if (c >= counts[e]) inv[i] = -1;
+    if (c >= (SCAN ? count_s[e] : counts[e])) inv[i] = -1;
   }
 }
 
@@ -496,7 +543,11 @@ extern "C" int moe_gate_topk(const void* x, int x_dtype, const float* Wg, const 
   else if (E <= 64) launch_topk<64, 1>(logits, S, E, k, norm, idx, w, blockhist, nblk, st);
   else if (E <= 128) launch_topk<64, 2>(logits, S, E, k, norm, idx, w, blockhist, nblk, st);
   else launch_topk<64, 4>(logits, S, E, k, norm, idx, w, blockhist, nblk, st);
-  hipLaunchKernelGGL(gate_scan, dim3((E + 3) / 4), dim3(256), 0, st, blockhist, nblk, E, k, blockbase, counts);
-  hipLaunchKernelGGL(gate_slots, dim3(nblk), dim3(GATE_TB), 0, st, idx, blockbase, counts, S, E, k, C, slot, inv);
+  if ((int64_t)nblk * k * E <= 16384) {   // every block reads all histograms itself: at most 64 KiB each
+    hipLaunchKernelGGL(gate_slots<true>, dim3(nblk), dim3(GATE_TB), 0, st, idx, blockhist, counts, S, E, k, C, slot, inv);
+  } else {
+    hipLaunchKernelGGL(gate_scan, dim3((E + 3) / 4), dim3(256), 0, st, blockhist, nblk, E, k, blockbase, counts);
+    hipLaunchKernelGGL(gate_slots<false>, dim3(nblk), dim3(GATE_TB), 0, st, idx, blockbase, counts, S, E, k, C, slot, inv);
+  }
   return moe::check_launch();
 }

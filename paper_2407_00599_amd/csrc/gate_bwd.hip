@@ -116,9 +116,9 @@ __global__ __launch_bounds__(256) void gate_dwg_reduce(const float* __restrict__
 
 // ---------------------------------------------------------------------------------------------
 // E <= 16: the whole gate backward except the final reduction in ONE kernel.  A block owns one
-// chunk of tokens (the unit of a dWg partial sum) and 128 CPT columns of M; a thread owns CPT
-// consecutive columns (CPT = 8 for up to 8 experts, 4 for up to 16, so that its slice of Wg and
-// its dWg accumulators fit in registers).  Sixteen tokens at a time, sixteen threads compute the
+// chunk of tokens (the unit of a dWg partial sum) and NTHR * 4 columns of M (one wave, 256 columns,
+// for up to 8 experts: many small blocks hide each other's phases; two waves for up to 16); a
+// thread owns 4 consecutive columns, so that its slice of Wg and its dWg accumulators fit in registers.  Sixteen tokens at a time, sixteen threads compute the
 // dlogits rows into LDS (column block 0 also stores them); then every thread reads its x and old
 // dx pieces of those tokens once and uses them twice:
 //     dWg partial[e][q] += x[t, q] dl[t, e]        dx[t, q] (+)= sum_e dl[t, e] Wg[q, e]
@@ -446,12 +446,12 @@ extern "C" int moe_gate_bwd(const float* dw, const float* w, const int32_t* idx,
     const int chunk = dwg_chunk(S, E);
     const int nchunk = (int)((S + chunk - 1) / chunk);
     float* partial = (float*)ws;
-    const int cols = E <= 8 ? 256 * 4 : 128 * 4;   // columns per block
+    const int cols = E <= 8 ? 64 * 4 : 128 * 4;   // columns per block
     const dim3 grid((unsigned)((M + cols - 1) / cols), (unsigned)nchunk);
 #define MOE_FUSED(BF, EC, CPT, NT) hipLaunchKernelGGL((gate_bwd_fused<BF, EC, CPT, NT>), grid, dim3(NT), 0, st, dw, w, idx, logits, x, \
                                                        Wg, S, M, E, k, norm, chunk, dlogits, dx, dx_accumulate, partial)
-    if (bf) { if (E <= 8) MOE_FUSED(true, 8, 4, 256); else MOE_FUSED(true, 16, 4, 128); }
-    else { if (E <= 8) MOE_FUSED(false, 8, 4, 256); else MOE_FUSED(false, 16, 4, 128); }
+    if (bf) { if (E <= 8) MOE_FUSED(true, 8, 4, 64); else MOE_FUSED(true, 16, 4, 128); }
+    else { if (E <= 8) MOE_FUSED(false, 8, 4, 64); else MOE_FUSED(false, 16, 4, 128); }
 #undef MOE_FUSED
     hipLaunchKernelGGL(gate_dwg_reduce, dim3((unsigned)((n + 63) / 64)), dim3(256), 0, st, partial, nchunk, M, E, dWg,
                        dgate_bias);

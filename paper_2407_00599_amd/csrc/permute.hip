@@ -36,11 +36,12 @@ __device__ __forceinline__ void st8(void* base, int64_t off, const float* f) {
 // buf[e, c, :] = (w?) * x[inv[e, c0 + c]/k, :]  or zeros, for the slots c0 <= c0 + c < c0 + Cr of every expert
 // (buf is [E, Cr, M]; the whole buffer when c0 = 0 and Cr = C).  One wave per output row.
 template <bool BF16>
-__global__ __launch_bounds__(256) void dispatch_rows(const void* __restrict__ x, const int32_t* __restrict__ inv,
-                                                     const float* __restrict__ w, void* __restrict__ buf,
-                                                     int64_t rows, int M, int k, int64_t C, int64_t c0, int64_t Cr) {
+__device__ __forceinline__ void dispatch_rows_body(int64_t blk, const void* __restrict__ x,
+                                                   const int32_t* __restrict__ inv, const float* __restrict__ w,
+                                                   void* __restrict__ buf, int64_t rows, int M, int k, int64_t C,
+                                                   int64_t c0, int64_t Cr) {
   const int lane = threadIdx.x & 63;
-  const int64_t row = (int64_t)blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6);
+  const int64_t row = blk * (blockDim.x >> 6) + (threadIdx.x >> 6);
   if (row >= rows) return;
   const int64_t e = row / Cr;
   const int a = inv[e * C + c0 + (row - e * Cr)];
@@ -71,6 +72,13 @@ __global__ __launch_bounds__(256) void dispatch_rows(const void* __restrict__ x,
       st8<BF16>(buf, dst + m, f);
     }
   }
+}
+
+template <bool BF16>
+__global__ __launch_bounds__(256) void dispatch_rows(const void* __restrict__ x, const int32_t* __restrict__ inv,
+                                                     const float* __restrict__ w, void* __restrict__ buf,
+                                                     int64_t rows, int M, int k, int64_t C, int64_t c0, int64_t Cr) {
+  dispatch_rows_body<BF16>((int64_t)blockIdx.x, x, inv, w, buf, rows, M, k, C, c0, Cr);
 }
 
 // y[t,:] = sum_j w[t,j] * sum_p Yret[p, idx[t,j], slot[t,j], :].  One wave per token.
@@ -261,13 +269,13 @@ __global__ __launch_bounds__(256) void combine_dw(const void* __restrict__ dy, c
 }
 
 template <bool BF16, int K, int P>
-__global__ __launch_bounds__(256) void combine_dw_kp(const void* __restrict__ dy, const void* __restrict__ Yret,
-                                                     const int32_t* __restrict__ idx, const int32_t* __restrict__ slot,
-                                                     float* __restrict__ dw, int64_t S, int M, int64_t C,
-                                                     int64_t part_stride) {
+__device__ __forceinline__ void combine_dw_kp_body(int64_t blk, const void* __restrict__ dy, const void* __restrict__ Yret,
+                                                   const int32_t* __restrict__ idx, const int32_t* __restrict__ slot,
+                                                   float* __restrict__ dw, int64_t S, int M, int64_t C,
+                                                   int64_t part_stride) {
   constexpr int NCH = (K * P >= 8) ? 1 : (K * P >= 4) ? 2 : 4;
   const int lane = threadIdx.x & 63;
-  const int64_t t = (int64_t)blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6);
+  const int64_t t = blk * (blockDim.x >> 6) + (threadIdx.x >> 6);
   if (t >= S) return;
   int64_t src[K];
   float dot[K];
@@ -319,6 +327,19 @@ __global__ __launch_bounds__(256) void combine_dw_kp(const void* __restrict__ dy
     for (int o = 32; o >= 1; o >>= 1) d += __shfl_xor(d, o, 64);
     if (lane == 0) dw[t * K + j] = d;
   }
+}
+
+// The whole combine backward in one launch: the first nb_rows workgroups write dYret (the weighted
+// dispatch of dy), the others the weight gradients.
+template <bool BF16, int K, int P>
+__global__ __launch_bounds__(256) void combine_bwd_kp(const void* __restrict__ dy, const void* __restrict__ Yret,
+                                                      const int32_t* __restrict__ idx, const int32_t* __restrict__ slot,
+                                                      const int32_t* __restrict__ inv, const float* __restrict__ w,
+                                                      void* __restrict__ dYret, float* __restrict__ dw, int64_t S, int M,
+                                                      int64_t C, int64_t part_stride, int64_t rows, int64_t nb_rows) {
+  const int64_t b = (int64_t)blockIdx.x;
+  if (b < nb_rows) dispatch_rows_body<BF16>(b, dy, inv, w, dYret, rows, M, K, C, (int64_t)0, C);
+  else combine_dw_kp_body<BF16, K, P>(b - nb_rows, dy, Yret, idx, slot, dw, S, M, C, part_stride);
 }
 
 }  // namespace
@@ -382,18 +403,22 @@ extern "C" int moe_combine_bwd(const void* dy, const void* Yret, int dtype, int 
   const int64_t ps = rows * M;
   const dim3 block(256), grid_r((unsigned)((rows + 3) / 4)), grid_t((unsigned)((S + 3) / 4));
   const bool bf = dtype == MOE_BF16;
-  if (dYret) {
-    if (bf) hipLaunchKernelGGL(dispatch_rows<true>, grid_r, block, 0, st, dy, inv, w, dYret, rows, M, k, C, (int64_t)0, C);
-    else hipLaunchKernelGGL(dispatch_rows<false>, grid_r, block, 0, st, dy, inv, w, dYret, rows, M, k, C, (int64_t)0, C);
-  }
+  const int64_t nb_rows = dYret ? (int64_t)grid_r.x : 0;
+  const dim3 grid_b((unsigned)(nb_rows + grid_t.x));
 #define COMBINE_DW_KP(K_, P_)                                                                                          \
   if (k == K_ && n_part == P_) {                                                                                       \
-    if (bf) hipLaunchKernelGGL((combine_dw_kp<true, K_, P_>), grid_t, block, 0, st, dy, Yret, idx, slot, dw, S, M, C, ps); \
-    else hipLaunchKernelGGL((combine_dw_kp<false, K_, P_>), grid_t, block, 0, st, dy, Yret, idx, slot, dw, S, M, C, ps);   \
+    if (bf) hipLaunchKernelGGL((combine_bwd_kp<true, K_, P_>), grid_b, block, 0, st, dy, Yret, idx, slot, inv, w, dYret, dw, \
+                               S, M, C, ps, rows, nb_rows);                                                            \
+    else hipLaunchKernelGGL((combine_bwd_kp<false, K_, P_>), grid_b, block, 0, st, dy, Yret, idx, slot, inv, w, dYret, dw,   \
+                            S, M, C, ps, rows, nb_rows);                                                               \
     return moe::check_launch();                                                                                        \
   }
   COMBINE_DW_KP(1, 1) COMBINE_DW_KP(1, 2) COMBINE_DW_KP(1, 4) COMBINE_DW_KP(2, 1) COMBINE_DW_KP(2, 2) COMBINE_DW_KP(2, 4)
 #undef COMBINE_DW_KP
+  if (dYret) {
+    if (bf) hipLaunchKernelGGL(dispatch_rows<true>, grid_r, block, 0, st, dy, inv, w, dYret, rows, M, k, C, (int64_t)0, C);
+    else hipLaunchKernelGGL(dispatch_rows<false>, grid_r, block, 0, st, dy, inv, w, dYret, rows, M, k, C, (int64_t)0, C);
+  }
   if (bf) hipLaunchKernelGGL(combine_dw<true>, grid_t, block, 0, st, dy, Yret, idx, slot, dw, S, M, k, C, n_part, ps);
   else hipLaunchKernelGGL(combine_dw<false>, grid_t, block, 0, st, dy, Yret, idx, slot, dw, S, M, k, C, n_part, ps);
   return moe::check_launch();
