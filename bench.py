@@ -22,7 +22,7 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0   # MI355X dense bf16 matrix peak
 HBM_PEAK_GBS = 8000.0
 # HBM bytes per grouped GEMM (mean of the 6 per step), from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of
 # this command scaled by the copy calibration; None where no such run has been made (see profiles/).
-MEASURED_TRAFFIC = {"layer_bf16": 228.1e6}   # profiles/bench_layer_bf16_gemm_pmc.md
+MEASURED_TRAFFIC = {"layer_bf16": 228.0e6}   # profiles/bench_layer_bf16_gemm_pmc.md
 
 
 def main():
