@@ -37,7 +37,7 @@ def test_dispatch_and_combine(S, M, E, k, C, dtype):
     api.moe_dispatch(to_dev(x), S, M, E, k, C, d_inv, d_w, bufw)
     assert rel_err(to_host(bufw), O.dispatch(x.val, inv, k, w)) <= (1e-6 if dtype == "f32" else 4e-3)
 
-    for n_part in (1, 3):
+    for n_part in (1, 2, 3, 4):
         Y = synth.store(rng.standard_normal((n_part, E, C, M)).astype(np.float32), dtype)
         y = torch.full((S, M), 7.0, dtype=tdt, device=DEV)
         api.moe_combine_fwd(to_dev(Y), n_part, S, M, E, k, C, d_idx, d_slot, d_w, y)
