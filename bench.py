@@ -33,6 +33,8 @@ def main():
     ap.add_argument("--config", default="layer_bf16", help="workload name from synth.CONFIGS")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--tile", type=int, default=0, help="FFN GEMM variant, see moe_ffn_set_tile (0 = auto)")
+    ap.add_argument("--unfused-dispatch", action="store_true",
+                    help="write the dispatched [E, C, M] buffer even when every expert is local (default: fused into the GEMMs)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 1 GiB device-to-device copy 5 times (known traffic, used to scale the "
                          "FETCH_SIZE / WRITE_SIZE counters when the run is profiled with rocprofv3 --pmc)")
@@ -102,9 +104,13 @@ def main():
         torch.cuda.synchronize()
         del src, dst
 
-    names = MoERankShape.STEPS
+    # With every expert on this rank no AlltoAll separates the gate from the experts, and the dispatch is
+    # fused into the expert GEMMs (token rows read through the inverse slot map: the same values, one
+    # launch and one [E, C, M] buffer less); otherwise the dispatch writes the send buffer.
+    fused_step = L.closed and not args.unfused_dispatch
+    names = MoERankShape.STEPS_FUSED if fused_step else MoERankShape.STEPS
     for _ in range(args.warmup):
-        L.step()
+        L.step(fused_step)
     torch.cuda.synchronize()
 
     K = args.steps
@@ -122,7 +128,7 @@ def main():
                 getattr(L, n)()
                 ev[s][i + 1].record()
         else:
-            L.step()
+            L.step(fused_step)
     torch.cuda.synchronize()
     t1 = time.perf_counter()
     ms_per_step = (t1 - t0) * 1e3 / K
@@ -136,7 +142,8 @@ def main():
     executed = sum(api.moe_ffn_executed_flops(dtc, L.n_src, L.G, L.C, cfg.M, cfg.H, L.n_esp, cnt_host, b) for b in (0, 1))
     flops_per_launch = executed / 6.0
     occupied = rows if cnt_host is None else int(np.minimum(cnt_host, L.C).sum())
-    gemm_ms = (per_call["ffn_fwd"] + per_call["ffn_bwd"]) / 6.0
+    fwd_name, bwd_name = ("ffn_fwd_gather", "ffn_bwd_gather") if fused_step else ("ffn_fwd", "ffn_bwd")
+    gemm_ms = (per_call[fwd_name] + per_call[bwd_name]) / 6.0
     achieved = flops_per_launch / (gemm_ms * 1e-3) / 1e12
     roofline = {"bound": "mfma", "achieved": round(achieved, 2), "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
                 "frac": round(achieved / MFMA_BF16_PEAK_TFLOPS, 4), "traffic": MEASURED_TRAFFIC.get(cfg.name),
@@ -160,7 +167,8 @@ def main():
             e1.record(); torch.cuda.synchronize()
             return e0.elapsed_time(e1) / reps
         fused = {"dispatch_plus_ffn_fwd_ms": round(timed(lambda: (L.dispatch(), L.ffn_fwd())), 4),
-                 "ffn_fwd_gather_ms": round(timed(L.ffn_fwd_gather), 4)}
+                 "ffn_fwd_gather_ms": round(timed(L.ffn_fwd_gather), 4),
+                 "ffn_bwd_ms": round(timed(L.ffn_bwd), 4), "ffn_bwd_gather_ms": round(timed(L.ffn_bwd_gather), 4)}
 
     cpu = None
     if small and not args.no_cpu_baseline and L.closed:
@@ -188,7 +196,7 @@ def main():
         "dtype": "bf16" if cfg.dtype == "bf16" else "f32", "data": "synthetic",
         "config": {"workload": f"{cfg.name}: S={L.S} tokens, M={cfg.M}, H={cfg.H} (H_local={L.Hl}), E={cfg.E} "
                                f"(G={L.G} local, n_src={L.n_src}), top-{cfg.k}, f={cfg.f}, C={L.C}; "
-                               f"gate+dispatch+FFN+combine fwd+bwd"},
+                               f"gate+dispatch+FFN+combine fwd+bwd" + (" (dispatch fused into the expert GEMMs)" if fused_step else "")},
         "roofline": roofline, "cpu_baseline": cpu,
         "per_call_ms": {k: round(v, 4) for k, v in per_call.items()}, "per_call_steps": len(probed),
         "fused_dispatch_fwd": fused,

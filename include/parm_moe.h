@@ -186,12 +186,23 @@ int moe_expert_ffn_fwd(const void* X, int dtype, const void* W1, const void* W2,
  *   x    [S, M]      dtype, device, in (token rows)
  *   inv  [E, C]      int32, device, in (from moe_gate_topk: t * k + j, or -1)
  *   the other arguments as in moe_expert_ffn_fwd with n_src = 1, G = E.
- * The backward call still takes the dispatched X (its weight gradient reduces over the slots),
- * so this entry point serves forward-only use; S * k must be below 2^31.  Errors as above. */
+ * S * k may not exceed 2^29 (MOE_EUNSUPPORTED).  Errors as above.
+ *
+ * moe_expert_ffn_bwd_gather is the matching backward: the weight gradient dW1 = X^T dZ reads its
+ * rows of X from the token matrix through the same map (the reduction index is the slot), so a
+ * training step needs no dispatched [E, C, M] buffer at all.  dX is still the slot-ordered
+ * [1, E, C, M] gradient, which moe_combine_fwd(w = NULL) turns into dx.  Same values as
+ * moe_expert_ffn_bwd on the dispatched buffer.  Other arguments as in moe_expert_ffn_bwd with
+ * n_src = 1, G = E. */
 int moe_expert_ffn_fwd_gather(const void* x, int dtype, int64_t S, const int32_t* inv, int k,
                               const void* W1, const void* W2, int E, int64_t C, int M, int H,
                               int esp_idx, int n_esp, const int32_t* row_counts,
                               void* Z, void* A, void* Y, void* stream);
+int moe_expert_ffn_bwd_gather(const void* dY, const void* x, int64_t S, const int32_t* inv, int k,
+                              const void* Z, const void* A, const void* W1, const void* W2,
+                              int dtype, int E, int64_t C, int M, int H, int esp_idx, int n_esp,
+                              const int32_t* row_counts,
+                              void* dX, void* dW1, void* dW2, void* ws, size_t ws_bytes, void* stream);
 
 int moe_expert_ffn_bwd(const void* dY, const void* X, const void* Z, const void* A,
                        const void* W1, const void* W2, int dtype,

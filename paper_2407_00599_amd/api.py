@@ -67,6 +67,9 @@ def lib() -> ctypes.CDLL:
         L.moe_expert_ffn_fwd_gather.restype = c_i
         L.moe_expert_ffn_fwd_gather.argtypes = [c_p, c_i, c_i64, c_p, c_i, c_p, c_p, c_i, c_i64, c_i, c_i, c_i, c_i,
                                                 c_p, c_p, c_p, c_p, c_p]
+        L.moe_expert_ffn_bwd_gather.restype = c_i
+        L.moe_expert_ffn_bwd_gather.argtypes = [c_p, c_p, c_i64, c_p, c_i, c_p, c_p, c_p, c_p, c_i, c_i, c_i64, c_i, c_i,
+                                                c_i, c_i, c_p, c_p, c_p, c_p, c_p, c_sz, c_p]
         L.moe_expert_ffn_bwd.restype = c_i
         L.moe_expert_ffn_bwd.argtypes = [c_p, c_p, c_p, c_p, c_p, c_p, c_i, c_i, c_i, c_i64, c_i, c_i, c_i, c_i,
                                          c_p, c_p, c_p, c_p, c_p, c_sz, c_p]
@@ -86,7 +89,7 @@ def lib() -> ctypes.CDLL:
 
 EXPORTED = [
     "moe_strerror", "moe_abi_version", "moe_capacity", "moe_gate_workspace_bytes", "moe_gate_topk",
-    "moe_dispatch", "moe_dispatch_slots", "moe_ffn_workspace_bytes", "moe_ffn_set_tile", "moe_ffn_executed_flops", "moe_expert_ffn_fwd", "moe_expert_ffn_fwd_gather", "moe_expert_ffn_bwd",
+    "moe_dispatch", "moe_dispatch_slots", "moe_ffn_workspace_bytes", "moe_ffn_set_tile", "moe_ffn_executed_flops", "moe_expert_ffn_fwd", "moe_expert_ffn_fwd_gather", "moe_expert_ffn_bwd", "moe_expert_ffn_bwd_gather",
     "moe_combine_fwd", "moe_combine_bwd", "moe_gate_bwd_workspace_bytes", "moe_gate_bwd", "moe_alpha_beta_fit",
     "moe_choose_schedule",
 ]
@@ -215,6 +218,14 @@ def moe_expert_ffn_bwd(dY, X, Z, A, W1, W2, n_src, G, C, M, H, esp_idx, n_esp, d
     _check(lib().moe_expert_ffn_bwd(_ptr(dY), _ptr(X), _ptr(Z), _ptr(A), _ptr(W1), _ptr(W2), dtype_code(X),
                                     n_src, G, C, M, H, esp_idx, n_esp, _ptr(row_counts), _ptr(dX), _ptr(dW1), _ptr(dW2),
                                     wp, wb, _stream()), "moe_expert_ffn_bwd")
+
+
+def moe_expert_ffn_bwd_gather(dY, x, inv, S, k, Z, A, W1, W2, E, C, M, H, esp_idx, n_esp, dX, dW1, dW2, ws,
+                              row_counts=None):
+    wp, wb = _ws_args(ws)
+    _check(lib().moe_expert_ffn_bwd_gather(_ptr(dY), _ptr(x), S, _ptr(inv), k, _ptr(Z), _ptr(A), _ptr(W1), _ptr(W2),
+                                           dtype_code(x), E, C, M, H, esp_idx, n_esp, _ptr(row_counts), _ptr(dX),
+                                           _ptr(dW1), _ptr(dW2), wp, wb, _stream()), "moe_expert_ffn_bwd_gather")
 
 
 def moe_combine_fwd(Yret, n_part, S, M, E, k, C, idx, slot, w, y):

@@ -49,7 +49,8 @@ struct GemmArgs {
   // gather[g * Cc + r] / gather_k (the gate's inverse slot map; negative = empty slot, a zero row)
   const int32_t* gather;
   int gather_k;
-  int64_t gather_rows;  // rows of the token matrix
+  uint32_t gather_magic;  // ceil(2^32 / gather_k): v / gather_k = umulhi(v, magic) for v < 2^29 (gather_k <= 8)
+  int64_t gather_rows;    // rows of the token matrix
   int G, n_src;
   int Cc;           // rows per chunk (capacity C)
   int R;            // n_src * Cc: virtual rows per expert
@@ -352,16 +353,32 @@ __global__ __launch_bounds__(WM * WN * 64) void ffn_gemm_bf16(const GemmArgs p) 
           const int col = m0 + r8 * 8;
           const uint32_t off0 = (uint32_t)(((chunk_row + kb * 8) * p.lda + col) * 2);
 #pragma unroll
-          for (int i = 0; i < 8; ++i)
-            sa.reg[b * 8 + i] = ldb16(rA, (kb * 8 + i < klim && col < p.Mdim) ? off0 + i * lda2 : OOB);
+          for (int i = 0; i < 8; ++i) {
+            uint32_t o = off0 + i * lda2;
+            bool ok = kb * 8 + i < klim && col < p.Mdim;
+            if (p.gather != nullptr && ok) {   // fused dispatch: the row is a token looked up through the slot map
+              const int64_t row = a_src_row(p, c0 + kb * 8 + i, g);
+              ok = row >= 0;
+              o = (uint32_t)((row * p.lda + col) * 2);
+            }
+            sa.reg[b * 8 + i] = ldb16(rA, ok ? o : OOB);
+          }
         }
       } else {
         const int kb4 = tid & 15, r8 = tid >> 4;
         const int col = m0 + r8 * 8;
         const uint32_t off0 = (uint32_t)(((chunk_row + kb4 * 4) * p.lda + col) * 2);
 #pragma unroll
-        for (int i = 0; i < 4; ++i)
-          sa.reg[i] = ldb16(rA, (kb4 * 4 + i < klim && col < p.Mdim) ? off0 + i * lda2 : OOB);
+        for (int i = 0; i < 4; ++i) {
+          uint32_t o = off0 + i * lda2;
+          bool ok = kb4 * 4 + i < klim && col < p.Mdim;
+          if (p.gather != nullptr && ok) {
+            const int64_t row = a_src_row(p, c0 + kb4 * 4 + i, g);
+            ok = row >= 0;
+            o = (uint32_t)((row * p.lda + col) * 2);
+          }
+          sa.reg[i] = ldb16(rA, ok ? o : OOB);
+        }
       }
     }
     // ---------------- B ----------------
@@ -733,11 +750,14 @@ __device__ __forceinline__ void ready(Frag& f) { asm volatile("" : "+v"(f.q)); }
 // WN = waves along n: 2 (4 waves, 128x128 per wave) or 4 (8 waves, 128x64 per wave, two per SIMD).
 // TMR = rows of the output tile: 256, or 192 (three 32-row blocks per wave; only for operands A
 // with k contiguous) for problems whose 256-row tiling would leave many compute units idle.
-template <int KIND, int EPI, int WN, int TMR>
+template <int KIND, int EPI, int WN, int TMR, bool GATHER = false>
 __device__ __forceinline__ void gemm_dma_tile(const GemmArgs& p, char* smem, int vb) {
   constexpr bool A_NC = (KIND == KIND_TN);                     // A has k as the slow index
   constexpr bool B_NC = (KIND == KIND_NN || KIND == KIND_TN);  // B has k as the slow index
   static_assert(TMR == 256 || (TMR == 192 && !A_NC && WN == 4), "unsupported tile height");
+  // GATHER: the k-slow A operand of a weight-gradient GEMM (X^T dZ) is the token matrix read through the
+  // inverse slot map (row r of the chunk is token gather[g C + r] / gather_k); n_src = 1.
+  static_assert(!GATHER || (KIND == KIND_TN && WN == 4), "row gather in the reduction: the 8-wave weight-gradient kernel only");
   constexpr int MB = TMR / 64, NBK = 8 / WN;     // 32x32 blocks per wave tile
   constexpr int RPW = 8 / WN;             // requests per wave per operand per k tile (16 in all)
 
@@ -783,7 +803,7 @@ __device__ __forceinline__ void gemm_dma_tile(const GemmArgs& p, char* smem, int
       const int k = 2 * q + (lane >> 5);
       const int col = m0 + (((lane & 31) ^ (4 * (k & 3))) * 8);
       a_k[j] = k;
-      a_req[j] = (col < p.Mdim) ? (uint32_t)(((int64_t)k * p.lda + col) * 2) : OOB;
+      a_req[j] = (col < p.Mdim) ? (uint32_t)(((int64_t)(GATHER ? 0 : k) * p.lda + col) * 2) : OOB;
     }
     if (!B_NC) {
       const int n = n0 + q * 16 + (lane >> 2);
@@ -797,6 +817,32 @@ __device__ __forceinline__ void gemm_dma_tile(const GemmArgs& p, char* smem, int
     }
   }
 
+  // GATHER: the four k-rows a wave requests per k tile (4 wave .. 4 wave + 3: requests j = 0, 1, lane halves)
+  // are the same for all its lanes, so their slot-map entries are read with scalar loads (issued as asm so
+  // that they stay scalar: nothing is added to the vector-memory queue whose length the waits below count).
+  // They are issued at the start of a k tile, have arrived at its second fragment wait (lgkmcnt(0)), and are
+  // turned into per-lane row offsets after the barrier, just before the A request that uses them.
+  uint32_t g_now[RPW];   // byte offset of the token row behind this lane's k-row of the next A request, or OOB
+  auto gather_fetch = [&](int kt, int (&dst)[4]) {
+    const int64_t last = (int64_t)p.G * p.Cc - 1;
+    const int64_t i0 = (int64_t)g * p.Cc + kt * DK + 4 * wave;   // rows past the count are never used
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const int64_t i = i0 + u < last ? i0 + u : last;
+      const uint32_t off = (uint32_t)__builtin_amdgcn_readfirstlane((int)(i * 4));
+      asm volatile("s_load_dword %0, %1, %2" : "=s"(dst[u]) : "s"(p.gather), "s"(off));
+    }
+  };
+  auto gather_rows = [&](int (&src)[4]) {   // after an lgkmcnt(0) wait that follows the fetch
+#pragma unroll
+    for (int u = 0; u < 4; ++u) asm volatile("" : "+s"(src[u]));
+#pragma unroll
+    for (int j = 0; j < RPW; ++j) {
+      const int iv = (lane >> 5) ? src[2 * j + 1] : src[2 * j];
+      const uint32_t tok = p.gather_k == 1 ? (uint32_t)iv : __umulhi((uint32_t)iv, p.gather_magic);
+      g_now[j] = (iv >= 0 && (int64_t)tok < p.gather_rows) ? tok * (uint32_t)(p.lda * 2) : OOB;
+    }
+  };
   // Requests of k tile kt into its stage, one instruction (1 KiB) at a time: which = 0 (A) / 1 (B),
   // j = 0..RPW-1.  Tiles past the end still issue (all lanes out of range, zeros are written) so that
   // the number of outstanding requests per wave is the same in every iteration.
@@ -816,8 +862,13 @@ __device__ __forceinline__ void gemm_dma_tile(const GemmArgs& p, char* smem, int
       lim = live ? p.Kdim - kt * DK : 0;
     }
     const int q = wave * RPW + j;
-    if (which == 0)
-      dma16(rA, reinterpret_cast<bf16_t*>(st + q * 1024), (a_req[j] != OOB && a_k[j] < lim) ? a_req[j] + add : OOB);
+    if (which == 0) {
+      if (GATHER)
+        dma16(rA, reinterpret_cast<bf16_t*>(st + q * 1024),
+              (a_req[j] != OOB && g_now[j] != OOB && a_k[j] < lim) ? a_req[j] + g_now[j] : OOB);
+      else
+        dma16(rA, reinterpret_cast<bf16_t*>(st + q * 1024), (a_req[j] != OOB && a_k[j] < lim) ? a_req[j] + add : OOB);
+    }
     else
       dma16(rB, reinterpret_cast<bf16_t*>(st + DREGION + q * 1024),
             (b_req[j] != OOB && b_k[j] < lim) ? b_req[j] + add : OOB);
@@ -919,10 +970,23 @@ __device__ __forceinline__ void gemm_dma_tile(const GemmArgs& p, char* smem, int
 #pragma unroll
       for (int q = 0; q < 16; ++q) acc[i][j][q] = 0.f;
 
-  request_half(0, 0); request_half(0, 1);
-  request_half(1, 0); request_half(1, 1);
-  request_half(2, 0); request_half(2, 1);
-  request_half(3, 0);
+  if (GATHER) {
+    int g_pro[4][4];
+#pragma unroll
+    for (int t4 = 0; t4 < 4; ++t4) gather_fetch(t4, g_pro[t4]);
+    __builtin_amdgcn_s_waitcnt(0xC07F);  // lgkmcnt(0)
+#pragma unroll
+    for (int t4 = 0; t4 < 4; ++t4) {
+      gather_rows(g_pro[t4]);
+      request_half(t4, 0);
+      if (t4 < 3) request_half(t4, 1);
+    }
+  } else {
+    request_half(0, 0); request_half(0, 1);
+    request_half(1, 0); request_half(1, 1);
+    request_half(2, 0); request_half(2, 1);
+    request_half(3, 0);
+  }
   // The padding test comes after the first requests are on their way, so that reading the counts
   // delays no tile that has work (a padding tile has fetched a few zeros for nothing).
   if (KIND != KIND_TN && p.cnt != nullptr) {
@@ -958,6 +1022,8 @@ __device__ __forceinline__ void gemm_dma_tile(const GemmArgs& p, char* smem, int
   int s0 = 0, s1 = 1, s3 = 3, s4 = 4;
   for (int kt = 0; kt < nk; ++kt) {
     frags_ready(0);
+    int g_idx[4];
+    if (GATHER) gather_fetch(kt + 4, g_idx);   // arrives by frags_ready(1)
     __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
     for (int i = 0; i < MB; ++i) {
@@ -975,6 +1041,7 @@ __device__ __forceinline__ void gemm_dma_tile(const GemmArgs& p, char* smem, int
     __builtin_amdgcn_s_waitcnt(vmcnt_imm(4 * RPW));
     __builtin_amdgcn_s_barrier();        // everyone is past tile kt-1, and tile kt+1 is complete
     __builtin_amdgcn_sched_barrier(0);
+    if (GATHER) gather_rows(g_idx);    // rows of tile kt+4
 #pragma unroll
     for (int i = 1; i < MB; ++i) {
       load_frags(s1, K0{}, i - 1);
@@ -994,23 +1061,23 @@ __device__ __forceinline__ void gemm_dma_tile(const GemmArgs& p, char* smem, int
                                  n0 + wn * (32 * NBK), lane);
 }
 
-template <int KIND, int EPI, int WN, int TMR = 256>
+template <int KIND, int EPI, int WN, int TMR = 256, bool GATHER = false>
 __global__ __launch_bounds__(128 * WN) void ffn_gemm_dma(const GemmArgs p) {
   __shared__ __attribute__((aligned(1024))) char smem[DSTAGES * DSTAGE];
-  gemm_dma_tile<KIND, EPI, WN, TMR>(p, smem, (int)blockIdx.x);
+  gemm_dma_tile<KIND, EPI, WN, TMR, GATHER>(p, smem, (int)blockIdx.x);
 }
 
 // The three GEMMs of the backward pass that only depend on dZ, in one launch: dX = dZ W1^T (row-tiled,
 // the long tiles, first in the grid) and the two weight gradients.  nbx and nbw are the (multiple-of-8)
 // workgroup counts of the first two problems.
-template <int TMR_X>
+template <int TMR_X, bool GATHER_W1 = false>   // GATHER_W1: the third problem reads its A operand through a slot map
 __global__ __launch_bounds__(512) void ffn_bwd_trio(const GemmArgs px, const GemmArgs pw2, const GemmArgs pw1, int nbx,
                                                     int nbw) {
   __shared__ __attribute__((aligned(1024))) char smem[DSTAGES * DSTAGE];
   const int b = (int)blockIdx.x;
   if (b < nbx) gemm_dma_tile<KIND_NT, EPI_STORE, 4, TMR_X>(px, smem, b);
   else if (b < nbx + nbw) gemm_dma_tile<KIND_TN, EPI_STORE, 4, 256>(pw2, smem, b - nbx);
-  else gemm_dma_tile<KIND_TN, EPI_STORE, 4, 256>(pw1, smem, b - nbx - nbw);
+  else gemm_dma_tile<KIND_TN, EPI_STORE, 4, 256, GATHER_W1>(pw1, smem, b - nbx - nbw);
 }
 
 // ------------------------------------------------------------------------------------------
@@ -1046,7 +1113,10 @@ __global__ __launch_bounds__(256) void ffn_gemm_f32(const GemmArgs p) {
         if (KIND == KIND_TN) { i = c & 63; k = c >> 6; } else { k = c & 15; i = c >> 4; }
         float v = 0.f;
         if (m0 + i < p.Mdim && k0 + k < Kd) {
-          if (KIND == KIND_TN) v = A[phys_row(k0 + k, g, p.G, p.Cc) * p.lda + m0 + i];
+          if (KIND == KIND_TN) {
+            const int64_t row = a_src_row(p, k0 + k, g);
+            if (row >= 0) v = A[row * p.lda + m0 + i];
+          }
           else {
             const int64_t row = a_src_row(p, m0 + i, g);
             if (row >= 0) v = A[row * p.lda + k0 + k];
@@ -1178,6 +1248,8 @@ void launch_gemm(GemmArgs a, int dtype, hipStream_t st) {
   const dim3 grid((unsigned)(((a.total_tiles + 7) / 8) * 8));
   if (t.tile_m == 192) {
     if constexpr (KIND != KIND_TN) hipLaunchKernelGGL((ffn_gemm_dma<KIND, EPI, 4, 192>), grid, dim3(512), 0, st, a);
+  } else if (t.dma && KIND == KIND_TN && a.gather != nullptr) {
+    if constexpr (KIND == KIND_TN) hipLaunchKernelGGL((ffn_gemm_dma<KIND, EPI, 4, 256, true>), grid, dim3(512), 0, st, a);
   } else if (t.dma && g_tile_pref != 2)
     hipLaunchKernelGGL((ffn_gemm_dma<KIND, EPI, 4>), grid, dim3(512), 0, st, a);
   else if (t.dma)
@@ -1295,20 +1367,26 @@ extern "C" int moe_expert_ffn_fwd(const void* X, int dtype, const void* W1, cons
   return ffn_fwd_impl(X, nullptr, 0, 0, dtype, W1, W2, n_src, G, C, M, H, esp_idx, n_esp, row_counts, Z, A, Y, stream);
 }
 
+// arguments of the fused-dispatch entry points: token matrix [S, M] and the inverse slot map
+static int check_gather(const void* x, int dtype, int64_t S, const int32_t* inv, int k, int M) {
+  MOE_REQUIRE(S >= 1 && k >= 1 && k <= MOE_MAX_K, MOE_EINVAL);
+  MOE_REQUIRE_PTR(x); MOE_REQUIRE_PTR(inv);
+  MOE_REQUIRE((int64_t)S * k <= (1ll << 29), MOE_EUNSUPPORTED);   // slot entries t k + j are divided by multiplication
+  if (dtype == MOE_BF16) MOE_REQUIRE((uint64_t)S * (uint64_t)M * 2 <= 0xFFFFFFF0ull, MOE_EUNSUPPORTED);
+  return MOE_OK;
+}
+
 extern "C" int moe_expert_ffn_fwd_gather(const void* x, int dtype, int64_t S, const int32_t* inv, int k, const void* W1,
                                          const void* W2, int E, int64_t C, int M, int H, int esp_idx, int n_esp,
                                          const int32_t* row_counts, void* Z, void* A, void* Y, void* stream) {
-  MOE_REQUIRE(S >= 1 && k >= 1 && k <= MOE_MAX_K, MOE_EINVAL);
-  MOE_REQUIRE_PTR(inv);
-  MOE_REQUIRE((int64_t)S * k < (1ll << 31), MOE_EUNSUPPORTED);
-  if (dtype == MOE_BF16) MOE_REQUIRE((uint64_t)S * (uint64_t)M * 2 <= 0xFFFFFFF0ull, MOE_EUNSUPPORTED);
+  if (int rc = check_gather(x, dtype, S, inv, k, M)) return rc;
   return ffn_fwd_impl(x, inv, k, S, dtype, W1, W2, 1, E, C, M, H, esp_idx, n_esp, row_counts, Z, A, Y, stream);
 }
 
-extern "C" int moe_expert_ffn_bwd(const void* dY, const void* X, const void* Z, const void* A, const void* W1,
-                                  const void* W2, int dtype, int n_src, int G, int64_t C, int M, int H, int esp_idx,
-                                  int n_esp, const int32_t* row_counts, void* dX, void* dW1, void* dW2, void* ws,
-                                  size_t ws_bytes, void* stream) {
+static int ffn_bwd_impl(const void* dY, const void* X, const int32_t* gather, int gather_k, int64_t gather_rows,
+                        const void* Z, const void* A, const void* W1, const void* W2, int dtype, int n_src, int G,
+                        int64_t C, int M, int H, int esp_idx, int n_esp, const int32_t* row_counts, void* dX, void* dW1,
+                        void* dW2, void* ws, size_t ws_bytes, void* stream) {
   if (int rc = check_ffn_shape(dtype, n_src, G, C, M, H, esp_idx, n_esp)) return rc;
   MOE_REQUIRE_PTR(dY); MOE_REQUIRE_PTR(X); MOE_REQUIRE_PTR(Z); MOE_REQUIRE_PTR(A); MOE_REQUIRE_PTR(W1);
   MOE_REQUIRE_PTR(W2); MOE_REQUIRE_PTR(dX); MOE_REQUIRE_PTR(dW1); MOE_REQUIRE_PTR(dW2);
@@ -1339,12 +1417,15 @@ extern "C" int moe_expert_ffn_bwd(const void* dY, const void* X, const void* Z, 
   // dW1[:, h0:h0+Hl] = X^T * dZ
   GemmArgs w1 = w2;
   w1.A = X; w1.lda = M;
+  w1.gather = gather; w1.gather_k = gather_k; w1.gather_rows = gather_rows;
+  w1.gather_magic = gather_k > 1 ? (uint32_t)((0x100000000ull + (uint64_t)gather_k - 1) / (uint64_t)gather_k) : 0u;
   w1.B = dZ; w1.ldb = Hl;
   w1.C = dW1; w1.ldc = H; w1.c_goff = (int64_t)M * H; w1.c_off = h0;
   w1.Mdim = M; w1.Ndim = Hl; w1.Kdim = a.R;
   // dX = dZ * W1[:, h0:h0+Hl]^T
   GemmArgs dx = w1;
   dx.A = dZ; dx.lda = Hl;
+  dx.gather = nullptr; dx.gather_k = 0; dx.gather_rows = 0; dx.gather_magic = 0;
   dx.B = W1; dx.ldb = H; dx.b_goff = (int64_t)M * H; dx.b_off = h0;
   dx.C = dX; dx.ldc = M; dx.c_goff = 0; dx.c_off = 0;
   dx.Mdim = a.R; dx.Ndim = M; dx.Kdim = Hl;
@@ -1355,8 +1436,13 @@ extern "C" int moe_expert_ffn_bwd(const void* dY, const void* X, const void* Z, 
     if (tx.dma && t2.dma && t1.dma) {
       const int nbx = (px.total_tiles + 7) / 8 * 8, nb2 = (p2.total_tiles + 7) / 8 * 8, nb1 = (p1.total_tiles + 7) / 8 * 8;
       const dim3 grid((unsigned)(nbx + nb2 + nb1));
-      if (tx.tile_m == 192) hipLaunchKernelGGL((ffn_bwd_trio<192>), grid, dim3(512), 0, st, px, p2, p1, nbx, nb2);
-      else hipLaunchKernelGGL((ffn_bwd_trio<256>), grid, dim3(512), 0, st, px, p2, p1, nbx, nb2);
+      if (gather) {
+        if (tx.tile_m == 192) hipLaunchKernelGGL((ffn_bwd_trio<192, true>), grid, dim3(512), 0, st, px, p2, p1, nbx, nb2);
+        else hipLaunchKernelGGL((ffn_bwd_trio<256, true>), grid, dim3(512), 0, st, px, p2, p1, nbx, nb2);
+      } else {
+        if (tx.tile_m == 192) hipLaunchKernelGGL((ffn_bwd_trio<192>), grid, dim3(512), 0, st, px, p2, p1, nbx, nb2);
+        else hipLaunchKernelGGL((ffn_bwd_trio<256>), grid, dim3(512), 0, st, px, p2, p1, nbx, nb2);
+      }
       return moe::check_launch();
     }
   }
@@ -1364,4 +1450,21 @@ extern "C" int moe_expert_ffn_bwd(const void* dY, const void* X, const void* Z, 
   launch_gemm<KIND_TN, EPI_STORE>(w1, dtype, st);
   launch_gemm<KIND_NT, EPI_STORE>(dx, dtype, st);
   return moe::check_launch();
+}
+
+extern "C" int moe_expert_ffn_bwd(const void* dY, const void* X, const void* Z, const void* A, const void* W1,
+                                  const void* W2, int dtype, int n_src, int G, int64_t C, int M, int H, int esp_idx,
+                                  int n_esp, const int32_t* row_counts, void* dX, void* dW1, void* dW2, void* ws,
+                                  size_t ws_bytes, void* stream) {
+  return ffn_bwd_impl(dY, X, nullptr, 0, 0, Z, A, W1, W2, dtype, n_src, G, C, M, H, esp_idx, n_esp, row_counts, dX, dW1,
+                      dW2, ws, ws_bytes, stream);
+}
+
+extern "C" int moe_expert_ffn_bwd_gather(const void* dY, const void* x, int64_t S, const int32_t* inv, int k,
+                                         const void* Z, const void* A, const void* W1, const void* W2, int dtype, int E,
+                                         int64_t C, int M, int H, int esp_idx, int n_esp, const int32_t* row_counts,
+                                         void* dX, void* dW1, void* dW2, void* ws, size_t ws_bytes, void* stream) {
+  if (int rc = check_gather(x, dtype, S, inv, k, M)) return rc;
+  return ffn_bwd_impl(dY, x, inv, k, S, Z, A, W1, W2, dtype, 1, E, C, M, H, esp_idx, n_esp, row_counts, dX, dW1, dW2, ws,
+                      ws_bytes, stream);
 }

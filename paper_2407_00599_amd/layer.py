@@ -61,16 +61,31 @@ class MoERankLayer:
         return self.y
 
     def forward_fused_dispatch(self, x_full, Wg, bias, W1, W2):
-        """Forward only, with the dispatch fused into the first GEMM (no [E, C, M] buffer is written);
-        backward() must not follow it, since the weight gradient reads the dispatched rows."""
+        """Forward with the dispatch fused into the first GEMM (no [E, C, M] buffer is written);
+        backward_fused_dispatch() is its backward."""
         S, M, E, k, C, H = self.S, self.M, self.E, self.k, self.C, self.H
         self.x = x_full[self.mp_idx * S:(self.mp_idx + 1) * S]
+        self.Wg, self.W1, self.W2 = Wg, W1, W2
         self.gate(x_full, Wg, bias)
         for j in range(self.n_esp):
             api.moe_expert_ffn_fwd_gather(self.x, self.inv, S, k, W1, W2, E, C, M, H, j, self.n_esp, self.Z[j],
                                           self.A[j], self.Yret[j], self.counts)
         api.moe_combine_fwd(self.Yret, self.n_esp, S, M, E, k, C, self.idx, self.slot, self.w, self.y)
         return self.y
+
+    def backward_fused_dispatch(self, dy):
+        """backward() without the dispatched buffer: the weight gradient of the first GEMM gathers its rows."""
+        S, M, E, k, C, H = self.S, self.M, self.E, self.k, self.C, self.H
+        api.moe_combine_bwd(dy, self.Yret, self.n_esp, S, M, E, k, C, self.idx, self.slot, self.inv, self.w,
+                            self.dYret, self.dw)
+        for j in range(self.n_esp):
+            api.moe_expert_ffn_bwd_gather(self.dYret, self.x, self.inv, S, k, self.Z[j], self.A[j], self.W1, self.W2,
+                                          E, C, M, H, j, self.n_esp, self.dbuf[j], self.dW1, self.dW2, self.ws,
+                                          self.counts)
+        api.moe_combine_fwd(self.dbuf, self.n_esp, S, M, E, k, C, self.idx, self.slot, None, self.dx)
+        api.moe_gate_bwd(self.dw, self.w, self.idx, self.logits, self.x, self.Wg, S, M, E, k, self.norm_topk,
+                         self.dlogits, self.dWg, self.dbias, self.dx, 1, self.ws)
+        return self.dx
 
     def backward(self, dy):
         S, M, E, k, C, H = self.S, self.M, self.E, self.k, self.C, self.H
@@ -250,6 +265,13 @@ class MoERankShape:
                                self.M, self.H, self.esp_idx, self.n_esp, self.dXout, self.dW1, self.dW2, self.ws,
                                self.row_counts)
 
+    def ffn_bwd_gather(self):
+        """ffn_bwd that reads the rows of X from the token matrix (every expert local); not one of STEPS."""
+        assert self.closed
+        api.moe_expert_ffn_bwd_gather(self.dYrecv, self.x, self.inv, self.S, self.k, self.Z, self.A, self.W1, self.W2,
+                                      self.E, self.C, self.M, self.H, self.esp_idx, self.n_esp, self.dXout, self.dW1,
+                                      self.dW2, self.ws, self.row_counts)
+
     def dispatch_bwd(self):
         api.moe_combine_fwd(self.dbuf, self.n_esp, self.S, self.M, self.E, self.k, self.C, self.idx, self.slot, None,
                             self.dx)
@@ -260,7 +282,9 @@ class MoERankShape:
                          self.dx, 1, self.ws)
 
     STEPS = ("gate", "dispatch", "ffn_fwd", "combine", "combine_bwd", "ffn_bwd", "dispatch_bwd", "gate_bwd")
+    # every expert local: the dispatch is fused into the expert GEMMs, no [E, C, M] input buffer is written
+    STEPS_FUSED = ("gate", "ffn_fwd_gather", "combine", "combine_bwd", "ffn_bwd_gather", "dispatch_bwd", "gate_bwd")
 
-    def step(self):
-        for name in self.STEPS:
+    def step(self, fused=False):
+        for name in (self.STEPS_FUSED if fused else self.STEPS):
             getattr(self, name)()

@@ -35,7 +35,7 @@ def test_every_declared_symbol_is_exported_and_bound(L):
     for n in names:                       # the Python binding has the same names
         if n not in ("moe_strerror", "moe_abi_version"):
             assert hasattr(api, n), n
-    assert L.moe_abi_version() == 4
+    assert L.moe_abi_version() == 5
 
 
 def test_error_strings(L):
@@ -127,6 +127,13 @@ def test_ffn_argument_checks(L):
     assert fwd_g(inv=U) == -3
     assert fwd_g(S=1 << 30, k=2) == -2             # S * k must stay below 2^31
     assert fwd_g(M=60) == -2
+    assert fwd_g(S=(1 << 28) + 1, k=2) == -2 and fwd_g(S=1 << 28, k=2, x=None) == -6
+
+    def bwd_g(x=A, S=16, inv=A, k=2, dW1=A, ws=A, wsb=1 << 30):
+        return L.moe_expert_ffn_bwd_gather(A, x, S, inv, k, A, A, A, A, 1, 2, 10, 64, 128, 0, 1, None, A, dW1, A, ws, wsb, None)
+    assert bwd_g(k=0) == -1 and bwd_g(S=0) == -1
+    assert bwd_g(inv=None) == -6 and bwd_g(x=U) == -3 and bwd_g(dW1=None) == -6
+    assert bwd_g(wsb=64) == -5 and bwd_g(ws=None) == -5
     assert L.moe_expert_ffn_bwd(A, A, A, A, A, A, 1, 1, 2, 10, 64, 128, 0, 1, None, A, A, None, A, 1 << 30, None) == -6
     assert L.moe_expert_ffn_bwd(A, A, A, None, A, A, 1, 1, 2, 10, 64, 128, 0, 1, None, A, A, A, A, 1 << 30, None) == -6
     assert L.moe_expert_ffn_bwd(A, A, A, A, A, A, 1, 1, 2, 10, 64, 128, 0, 1, None, A, A, A, A, 64, None) == -5

@@ -1,7 +1,7 @@
-"""GPU parity: expert FFN forward with the dispatch fused into the first GEMM (rows read from the
-token matrix through the inverse slot map) against the CPU checker, and value for value against
-the unfused pair of calls (dispatch, then the FFN), which computes the same products in the same
-order from the same bits."""
+"""GPU parity: expert FFN forward and backward with the dispatch fused into the GEMMs (rows read from
+the token matrix through the inverse slot map: by the first GEMM, and by the weight gradient of the
+first GEMM) against the CPU checker, and value for value against the unfused calls (dispatch, then the
+FFN), which compute the same products in the same order from the same bits."""
 import numpy as np
 import pytest
 import torch
@@ -75,6 +75,37 @@ def test_fused_dispatch_forward(S, k, E, C, M, H, n_esp, esp_idx, dtype, tile, f
     # empty slots give exactly zero
     empty = torch.from_numpy(inv < 0).to(DEV)
     assert not Z[0][empty].any() and not Y[0][empty].any()
+
+    # backward: dY has zero rows at the empty slots (as the combine backward writes it)
+    dYn = rng.standard_normal((1, E, C, M)).astype(np.float32)
+    dYn[0][inv < 0] = 0
+    dY = synth.store(dYn, dtype); dYd = to_dev(dY)
+    dt = api.MOE_BF16 if dtype == "bf16" else api.MOE_F32
+    ws = torch.empty(api.moe_ffn_workspace_bytes(dt, 1, E, C, M, H, n_esp), dtype=torch.uint8, device=DEV)
+    outs = []
+    api.moe_ffn_set_tile(tile)
+    try:
+        for fused in (True, False):
+            dX = new(1, E, C, M); dW1 = torch.full((E, M, H), 3.0, dtype=tdt, device=DEV)
+            dW2 = torch.full((E, H, M), 3.0, dtype=tdt, device=DEV)
+            if fused:
+                api.moe_expert_ffn_bwd_gather(dYd, xd, invd, S, k, Z, A, W1d, W2d, E, C, M, H, esp_idx, n_esp, dX, dW1,
+                                              dW2, ws, cnt)
+            else:
+                api.moe_expert_ffn_bwd(dYd, buf.view(1, E, C, M), Z2, A2, W1d, W2d, 1, E, C, M, H, esp_idx, n_esp, dX,
+                                       dW1, dW2, ws, cnt)
+            torch.cuda.synchronize()
+            outs.append((dX, dW1, dW2))
+    finally:
+        api.moe_ffn_set_tile(0)
+    for a, b in zip(*outs):
+        assert torch.equal(a, b)
+    rdX, rdW1, rdW2 = O.expert_ffn_bwd(dY.val, X, W1.val, W2.val, esp_idx, n_esp)
+    hs = slice(esp_idx * Hl, (esp_idx + 1) * Hl)
+    dX, dW1, dW2 = outs[0]
+    assert rel_err(to_host(dX), rdX) <= tol
+    assert rel_err(to_host(dW1)[:, :, hs], rdW1) <= tol
+    assert rel_err(to_host(dW2)[:, hs, :], rdW2) <= tol
 
 
 def test_out_of_range_indices_read_as_empty_slots():

@@ -83,7 +83,7 @@ def test_forward_with_fused_dispatch_is_the_same_forward(name, n_esp):
     """Real routing from the gate: the forward that reads token rows through the inverse slot map gives the
     bits of the forward that dispatches first, and matches the checker."""
     cfg = synth.CONFIGS[name]
-    L, r, g, args, _ = run_layer(cfg, n_esp, 1)
+    L, r, g, args, run_dy = run_layer(cfg, n_esp, 1)
     ref = {n: getattr(L, n).clone() for n in ("Z", "A", "Yret", "y")}
     for n in ref:
         getattr(L, n).fill_(5.0)
@@ -93,3 +93,11 @@ def test_forward_with_fused_dispatch_is_the_same_forward(name, n_esp):
     for n, t in ref.items():
         assert torch.equal(getattr(L, n), t), n
     assert rel_err(to_host(L.y), r["y"]) <= TOL[cfg.dtype]
+    # and the backward that reads the rows of X through the map: the same gradients, bit for bit
+    gref = {n: getattr(L, n).clone() for n in ("dx", "dW1", "dW2", "dWg", "dbuf", "dw")}
+    for n in gref:
+        getattr(L, n).fill_(5.0)
+    L.backward_fused_dispatch(run_dy)
+    torch.cuda.synchronize()
+    for n, t in gref.items():
+        assert torch.equal(getattr(L, n), t), n
