@@ -1,7 +1,7 @@
 #!/usr/bin/env python3
 """Benchmark of one rank's MoE-layer step (gate, dispatch, expert FFN, combine; fwd+bwd) on ONE MI355X.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config layer_bf16] [--no-cpu-baseline]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config layer_bf16] [--no-cpu-baseline] [--unfused-dispatch]
 
 A step is one pass of the whole hot path over one batch of seeded synthetic input that is
 already resident in HBM.  Prints ONE JSON line: tokens/s of the layer fwd+bwd, the roofline of
@@ -22,7 +22,7 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0   # MI355X dense bf16 matrix peak
 HBM_PEAK_GBS = 8000.0
 # HBM bytes per grouped GEMM (mean of the 6 per step), from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of
 # this command scaled by the copy calibration; None where no such run has been made (see profiles/).
-MEASURED_TRAFFIC = {"layer_bf16": 228.0e6}   # profiles/bench_layer_bf16_gemm_pmc.md
+MEASURED_TRAFFIC = {"layer_bf16": 222.9e6}   # profiles/bench_layer_bf16_gemm_pmc.md
 
 
 def main():
@@ -35,6 +35,8 @@ def main():
     ap.add_argument("--tile", type=int, default=0, help="FFN GEMM variant, see moe_ffn_set_tile (0 = auto)")
     ap.add_argument("--unfused-dispatch", action="store_true",
                     help="write the dispatched [E, C, M] buffer even when every expert is local (default: fused into the GEMMs)")
+    ap.add_argument("--no-extras", action="store_true",
+                    help="skip the fused / unfused dispatch comparison after the timed region (profiling runs)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 1 GiB device-to-device copy 5 times (known traffic, used to scale the "
                          "FETCH_SIZE / WRITE_SIZE counters when the run is profiled with rocprofv3 --pmc)")
@@ -157,7 +159,7 @@ def main():
     # Forward with the dispatch fused into the first GEMM (outside the timed region, every expert local):
     # the pair of calls it replaces against the one call, events around 20 repetitions of each
     fused = None
-    if L.closed:
+    if L.closed and not args.no_extras:
         def timed(fn, reps=20):
             e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
             fn(); torch.cuda.synchronize()
