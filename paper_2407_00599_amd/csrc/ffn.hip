@@ -1465,6 +1465,7 @@ extern "C" int moe_expert_ffn_bwd_gather(const void* dY, const void* x, int64_t 
                                          int64_t C, int M, int H, int esp_idx, int n_esp, const int32_t* row_counts,
                                          void* dX, void* dW1, void* dW2, void* ws, size_t ws_bytes, void* stream) {
   if (int rc = check_gather(x, dtype, S, inv, k, M)) return rc;
+  MOE_REQUIRE((int64_t)E * C <= (1ll << 29), MOE_EUNSUPPORTED);   // 32-bit byte offsets into the slot map
   return ffn_bwd_impl(dY, x, inv, k, S, Z, A, W1, W2, dtype, 1, E, C, M, H, esp_idx, n_esp, row_counts, dX, dW1, dW2, ws,
                       ws_bytes, stream);
 }
