@@ -28,8 +28,9 @@ MEASURED_TRAFFIC = {"layer_bf16": 222.9e6}   # profiles/bench_layer_bf16_gemm_pm
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=30)
-    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=200,
+                    help="untimed steps first: the GPU needs about 50 steps (30 ms) of this load before its clocks settle")
     ap.add_argument("--config", default="layer_bf16", help="workload name from synth.CONFIGS")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--tile", type=int, default=0, help="FFN GEMM variant, see moe_ffn_set_tile (0 = auto)")
