@@ -176,7 +176,8 @@ int moe_expert_ffn_fwd(const void* X, int dtype, const void* W1, const void* W2,
                        const int32_t* row_counts, void* Z, void* A, void* Y, void* stream);
 
 /* Forward with the dispatch fused into the first GEMM, for a rank that holds every expert
- * (N_EP = N_ESP-sharded or not, no AlltoAll between gate and experts; Section III-B notes that
+ * (N_EP = 1; the ESP shards may still run one after the other: no AlltoAll between gate and
+ * experts; Section III-B notes that
  * the local duplication before the AlltoAll is virtual, and without an AlltoAll the [E,C,M]
  * buffer itself need not exist): row c of expert e of the first GEMM is read straight from the
  * token matrix through the gate's inverse slot map,
@@ -186,7 +187,7 @@ int moe_expert_ffn_fwd(const void* X, int dtype, const void* W1, const void* W2,
  *   x    [S, M]      dtype, device, in (token rows)
  *   inv  [E, C]      int32, device, in (from moe_gate_topk: t * k + j, or -1)
  *   the other arguments as in moe_expert_ffn_fwd with n_src = 1, G = E.
- * S * k may not exceed 2^29 (MOE_EUNSUPPORTED).  Errors as above.
+ * S * k may not exceed 2^29, and E * C not for the backward (MOE_EUNSUPPORTED).  Errors as above.
  *
  * moe_expert_ffn_bwd_gather is the matching backward: the weight gradient dW1 = X^T dZ reads its
  * rows of X from the token matrix through the same map (the reduction index is the slot), so a
