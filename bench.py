@@ -29,8 +29,10 @@ def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=200)
-    ap.add_argument("--warmup", type=int, default=200,
-                    help="untimed steps first: the GPU needs about 50 steps (30 ms) of this load before its clocks settle")
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--settle-steps", type=int, default=200,
+                    help="untimed steps before the warm-up steps: the GPU needs about 50 steps (30 ms) of this load "
+                         "before its clocks settle; reported as settle_steps")
     ap.add_argument("--config", default="layer_bf16", help="workload name from synth.CONFIGS")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--tile", type=int, default=0, help="FFN GEMM variant, see moe_ffn_set_tile (0 = auto)")
@@ -112,7 +114,7 @@ def main():
     # launch and one [E, C, M] buffer less); otherwise the dispatch writes the send buffer.
     fused_step = L.closed and not args.unfused_dispatch
     names = MoERankShape.STEPS_FUSED if fused_step else MoERankShape.STEPS
-    for _ in range(args.warmup):
+    for _ in range(args.settle_steps + args.warmup):
         L.step(fused_step)
     torch.cuda.synchronize()
 
@@ -194,7 +196,7 @@ def main():
 
     out = {
         "metric": "MoE-layer fwd+bwd tokens/s (1 GPU)", "value": round(L.S / (ms_per_step * 1e-3), 1), "unit": "tokens/s",
-        "n_gpus": 1, "steps": K, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4),
+        "n_gpus": 1, "steps": K, "warmup": args.warmup, "settle_steps": args.settle_steps, "ms_per_step": round(ms_per_step, 4),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16" if cfg.dtype == "bf16" else "f32", "data": "synthetic",
         "config": {"workload": f"{cfg.name}: S={L.S} tokens, M={cfg.M}, H={cfg.H} (H_local={L.Hl}), E={cfg.E} "
