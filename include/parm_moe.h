@@ -33,7 +33,7 @@
  *   - MP and ESP are plain integers: (mp_idx, n_mp) picks this rank's block of the token
  *     rows, (esp_idx, n_esp) picks the hidden slice [esp_idx*H/n_esp, (esp_idx+1)*H/n_esp)
  *     of the FULL weight tensors W1 [G,M,H] and W2 [G,H,M].
- *   - Limits: 1 <= k <= 8, k <= E <= 256, M % 8 == 0, H_l % 8 == 0 (bf16) or % 4 (fp32).
+ *   - Limits: 1 <= k <= 8, k <= E <= 256, M % 8 == 0, H_l % 8 == 0 (both storage types).
  */
 #ifndef PARM_MOE_H
 #define PARM_MOE_H
@@ -72,8 +72,9 @@ int64_t moe_capacity(int64_t S, int E, int k, double f);
  * Gate: Section II-A "Gating Function" (linear layer, softmax, top-k, capacity T) on the
  * MP slice of Section III-B.
  *
- *   x         [S_total, M] activations (x_dtype), or NULL: then `logits` is an INPUT
- *   Wg        [M, E] fp32 gate weight (ignored when x is NULL)
+ *   x         [S_total, M] activations (x_dtype), or NULL: then `logits` is an INPUT and M,
+ *             x_dtype and Wg are ignored
+ *   Wg        [M, E] fp32 gate weight
  *   gate_bias [E] fp32 or NULL, added to the logits
  *   S_total, n_mp, mp_idx: the rank gates rows [mp_idx*S, (mp_idx+1)*S), S = S_total/n_mp
  *   norm_topk 1: weights = softmax over the k selected logits; 0: full-softmax probability
@@ -97,8 +98,8 @@ int moe_gate_topk(const void* x, int x_dtype, const float* Wg, const float* gate
                   void* ws, size_t ws_bytes, void* stream);
 
 /* ---------------------------------------------------------------------------------------
- * Dispatch: Section II-A, "each row of G (G[i,:,:]) corresponds to the data that should be
- * dispatched to expert i".  buf[e,c,:] = x[t,:] for the occupant (t,j) = inv[e,c], zeros for
+ * Dispatch: Section II-A defines G in R^{E x T x M}, whose slice G[i,:,:] holds the tokens that
+ * go to expert i.  buf[e,c,:] = x[t,:] for the occupant (t,j) = inv[e,c], zeros for
  * empty slots; with w != NULL rows are scaled by w[t,j] (fp32 multiply, rounded to dtype).
  * buf [E,C,M] viewed [N_EP, G, C, M] is the send buffer of the EP&ESP-AlltoAll (Section
  * III-C); the "Dump" that duplicates it N_ESP times is an alias of the same memory.
@@ -154,26 +155,29 @@ int moe_dispatch_slots(const void* x, int dtype, int64_t S, int M, int E, int k,
  * forward call needs none.  0 for invalid shapes. */
 size_t moe_ffn_workspace_bytes(int dtype, int n_src, int G, int64_t C, int M, int H, int n_esp);
 
-/* Tuning knob for the bf16 grouped GEMMs.  0 = choose per GEMM from its tile count (default);
- * 1 = 128x128 tiles, register-staged; 2 = 256x256 LDS-DMA kernel with 4 waves; 6 = the same
- * with 8 waves (the default for all but tiny problems); 7 = the 8-wave kernel with 192-row tiles
- * wherever the operand layout allows (auto picks it when it fills the chip better);
- * 3, 4, 5 = 256x256 register-staged variants kept for comparison.  Process-wide; affects speed only, never results beyond fp32
- * summation order.  Returns MOE_EINVAL for other values. */
-int moe_ffn_set_tile(int tile);
+/* Tile hint of the bf16 grouped GEMMs, an argument of every expert-FFN call.  It selects among
+ * kernels that compute the same products and may change the fp32 summation order, nothing else:
+ *   MOE_TILE_AUTO   per GEMM from its tile count (what a caller should pass)
+ *   MOE_TILE_SMALL  128 x 128 output tiles, register-staged kernel (what AUTO picks for tiny GEMMs;
+ *                   this kernel ignores row_counts)
+ *   MOE_TILE_256    256 x 256 tiles, LDS-DMA kernel
+ *   MOE_TILE_192    the same kernel with 192-row tiles wherever the operand layout allows (the
+ *                   row-tiled GEMMs; AUTO picks it when it fills the chip's compute units better)
+ * Other values: MOE_EINVAL.  Ignored for fp32. */
+enum { MOE_TILE_AUTO = 0, MOE_TILE_SMALL = 1, MOE_TILE_256 = 2, MOE_TILE_192 = 3 };
 
 /* Floating-point operations the forward (backward = 0: 2 GEMMs) or backward (backward = 1: 4 GEMMs)
- * call multiplies out for this shape under the current tile setting: 2 * M * H_l per multiplied row
+ * call multiplies out for this shape and tile hint: 2 * M * H_l per multiplied row
  * and GEMM, where a row counts if it lies in a row tile that is not skipped (row-tiled GEMMs) or
  * below the count (weight-gradient reductions, n_src = 1).  row_counts_host is a HOST copy of the
  * row_counts passed to the calls, or NULL (every row is multiplied).  Pure host arithmetic, used by
  * the benchmark to price the matrix pipes by executed work.  0 for invalid shapes. */
 double moe_ffn_executed_flops(int dtype, int n_src, int G, int64_t C, int M, int H, int n_esp,
-                              const int32_t* row_counts_host, int backward);
+                              const int32_t* row_counts_host, int tile, int backward);
 
 int moe_expert_ffn_fwd(const void* X, int dtype, const void* W1, const void* W2,
                        int n_src, int G, int64_t C, int M, int H, int esp_idx, int n_esp,
-                       const int32_t* row_counts, void* Z, void* A, void* Y, void* stream);
+                       const int32_t* row_counts, int tile, void* Z, void* A, void* Y, void* stream);
 
 /* Forward with the dispatch fused into the first GEMM, for a rank that holds every expert
  * (N_EP = 1; the ESP shards may still run one after the other: no AlltoAll between gate and
@@ -197,18 +201,18 @@ int moe_expert_ffn_fwd(const void* X, int dtype, const void* W1, const void* W2,
  * n_src = 1, G = E. */
 int moe_expert_ffn_fwd_gather(const void* x, int dtype, int64_t S, const int32_t* inv, int k,
                               const void* W1, const void* W2, int E, int64_t C, int M, int H,
-                              int esp_idx, int n_esp, const int32_t* row_counts,
+                              int esp_idx, int n_esp, const int32_t* row_counts, int tile,
                               void* Z, void* A, void* Y, void* stream);
 int moe_expert_ffn_bwd_gather(const void* dY, const void* x, int64_t S, const int32_t* inv, int k,
                               const void* Z, const void* A, const void* W1, const void* W2,
                               int dtype, int E, int64_t C, int M, int H, int esp_idx, int n_esp,
-                              const int32_t* row_counts,
+                              const int32_t* row_counts, int tile,
                               void* dX, void* dW1, void* dW2, void* ws, size_t ws_bytes, void* stream);
 
 int moe_expert_ffn_bwd(const void* dY, const void* X, const void* Z, const void* A,
                        const void* W1, const void* W2, int dtype,
                        int n_src, int G, int64_t C, int M, int H, int esp_idx, int n_esp,
-                       const int32_t* row_counts,
+                       const int32_t* row_counts, int tile,
                        void* dX, void* dW1, void* dW2, void* ws, size_t ws_bytes, void* stream);
 
 /* ---------------------------------------------------------------------------------------

@@ -14,6 +14,7 @@ import os
 import torch
 
 MOE_F32, MOE_BF16 = 0, 1
+MOE_TILE_AUTO, MOE_TILE_SMALL, MOE_TILE_256, MOE_TILE_192 = 0, 1, 2, 3
 _PKG = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_PKG, "libparm_moe.so")
 
@@ -58,21 +59,19 @@ def lib() -> ctypes.CDLL:
         L.moe_dispatch_slots.restype = c_i
         L.moe_dispatch_slots.argtypes = [c_p, c_i, c_i64, c_i, c_i, c_i, c_i64, c_i64, c_i64, c_p, c_p, c_p, c_p]
         L.moe_ffn_executed_flops.restype = ctypes.c_double
-        L.moe_ffn_executed_flops.argtypes = [c_i, c_i, c_i, c_i64, c_i, c_i, c_i, c_p, c_i]
-        L.moe_ffn_set_tile.restype = c_i
-        L.moe_ffn_set_tile.argtypes = [c_i]
+        L.moe_ffn_executed_flops.argtypes = [c_i, c_i, c_i, c_i64, c_i, c_i, c_i, c_p, c_i, c_i]
         L.moe_expert_ffn_fwd.restype = c_i
         L.moe_expert_ffn_fwd.argtypes = [c_p, c_i, c_p, c_p, c_i, c_i, c_i64, c_i, c_i, c_i, c_i,
-                                         c_p, c_p, c_p, c_p, c_p]
+                                         c_p, c_i, c_p, c_p, c_p, c_p]
         L.moe_expert_ffn_fwd_gather.restype = c_i
         L.moe_expert_ffn_fwd_gather.argtypes = [c_p, c_i, c_i64, c_p, c_i, c_p, c_p, c_i, c_i64, c_i, c_i, c_i, c_i,
-                                                c_p, c_p, c_p, c_p, c_p]
+                                                c_p, c_i, c_p, c_p, c_p, c_p]
         L.moe_expert_ffn_bwd_gather.restype = c_i
         L.moe_expert_ffn_bwd_gather.argtypes = [c_p, c_p, c_i64, c_p, c_i, c_p, c_p, c_p, c_p, c_i, c_i, c_i64, c_i, c_i,
-                                                c_i, c_i, c_p, c_p, c_p, c_p, c_p, c_sz, c_p]
+                                                c_i, c_i, c_p, c_i, c_p, c_p, c_p, c_p, c_sz, c_p]
         L.moe_expert_ffn_bwd.restype = c_i
         L.moe_expert_ffn_bwd.argtypes = [c_p, c_p, c_p, c_p, c_p, c_p, c_i, c_i, c_i, c_i64, c_i, c_i, c_i, c_i,
-                                         c_p, c_p, c_p, c_p, c_p, c_sz, c_p]
+                                         c_p, c_i, c_p, c_p, c_p, c_p, c_sz, c_p]
         L.moe_combine_fwd.restype = c_i
         L.moe_combine_fwd.argtypes = [c_p, c_i, c_i, c_i64, c_i, c_i, c_i, c_i64, c_p, c_p, c_p, c_p, c_p]
         L.moe_combine_bwd.restype = c_i
@@ -89,7 +88,8 @@ def lib() -> ctypes.CDLL:
 
 EXPORTED = [
     "moe_strerror", "moe_abi_version", "moe_capacity", "moe_gate_workspace_bytes", "moe_gate_topk",
-    "moe_dispatch", "moe_dispatch_slots", "moe_ffn_workspace_bytes", "moe_ffn_set_tile", "moe_ffn_executed_flops", "moe_expert_ffn_fwd", "moe_expert_ffn_fwd_gather", "moe_expert_ffn_bwd", "moe_expert_ffn_bwd_gather",
+    "moe_dispatch", "moe_dispatch_slots", "moe_ffn_workspace_bytes", "moe_ffn_executed_flops", "moe_expert_ffn_fwd", "moe_expert_ffn_fwd_gather",
+    "moe_expert_ffn_bwd", "moe_expert_ffn_bwd_gather",
     "moe_combine_fwd", "moe_combine_bwd", "moe_gate_bwd_workspace_bytes", "moe_gate_bwd", "moe_alpha_beta_fit",
     "moe_choose_schedule",
 ]
@@ -147,10 +147,6 @@ def moe_gate_bwd_workspace_bytes(S, M, E) -> int:
     return int(lib().moe_gate_bwd_workspace_bytes(S, M, E))
 
 
-def moe_ffn_set_tile(tile: int):
-    _check(lib().moe_ffn_set_tile(tile), "moe_ffn_set_tile")
-
-
 def moe_gate_topk(x, Wg, gate_bias, S_total, M, E, k, C, mp_idx, n_mp, norm_topk,
                   logits, idx, slot, w, inv, counts, ws):
     wp, wb = _ws_args(ws)
@@ -191,7 +187,7 @@ def moe_dispatch_slots(x, S, M, E, k, C, c0, c1, inv, w, buf):
                                     _stream()), "moe_dispatch_slots")
 
 
-def moe_ffn_executed_flops(dtype, n_src, G, C, M, H, n_esp, row_counts_host=None, backward=False) -> float:
+def moe_ffn_executed_flops(dtype, n_src, G, C, M, H, n_esp, row_counts_host=None, backward=False, tile=0) -> float:
     """row_counts_host: a host int32 array [n_src, G] (numpy or CPU tensor) or None."""
     ptr = None
     if row_counts_host is not None:
@@ -199,32 +195,33 @@ def moe_ffn_executed_flops(dtype, n_src, G, C, M, H, n_esp, row_counts_host=None
         arr = np.ascontiguousarray(np.asarray(row_counts_host, dtype=np.int32))
         assert arr.size == n_src * G
         ptr = arr.ctypes.data_as(ctypes.c_void_p)
-    return float(lib().moe_ffn_executed_flops(dtype, n_src, G, C, M, H, n_esp, ptr, int(backward)))
+    return float(lib().moe_ffn_executed_flops(dtype, n_src, G, C, M, H, n_esp, ptr, tile, int(backward)))
 
 
-def moe_expert_ffn_fwd(X, W1, W2, n_src, G, C, M, H, esp_idx, n_esp, Z, A, Y, row_counts=None):
+def moe_expert_ffn_fwd(X, W1, W2, n_src, G, C, M, H, esp_idx, n_esp, Z, A, Y, row_counts=None, tile=0):
     _check(lib().moe_expert_ffn_fwd(_ptr(X), dtype_code(X), _ptr(W1), _ptr(W2), n_src, G, C, M, H, esp_idx, n_esp,
-                                    _ptr(row_counts), _ptr(Z), _ptr(A), _ptr(Y), _stream()), "moe_expert_ffn_fwd")
+                                    _ptr(row_counts), tile, _ptr(Z), _ptr(A), _ptr(Y), _stream()), "moe_expert_ffn_fwd")
 
 
-def moe_expert_ffn_fwd_gather(x, inv, S, k, W1, W2, E, C, M, H, esp_idx, n_esp, Z, A, Y, row_counts=None):
+def moe_expert_ffn_fwd_gather(x, inv, S, k, W1, W2, E, C, M, H, esp_idx, n_esp, Z, A, Y, row_counts=None, tile=0):
     _check(lib().moe_expert_ffn_fwd_gather(_ptr(x), dtype_code(x), S, _ptr(inv), k, _ptr(W1), _ptr(W2), E, C, M, H,
-                                           esp_idx, n_esp, _ptr(row_counts), _ptr(Z), _ptr(A), _ptr(Y), _stream()),
+                                           esp_idx, n_esp, _ptr(row_counts), tile, _ptr(Z), _ptr(A), _ptr(Y), _stream()),
            "moe_expert_ffn_fwd_gather")
 
 
-def moe_expert_ffn_bwd(dY, X, Z, A, W1, W2, n_src, G, C, M, H, esp_idx, n_esp, dX, dW1, dW2, ws, row_counts=None):
+def moe_expert_ffn_bwd(dY, X, Z, A, W1, W2, n_src, G, C, M, H, esp_idx, n_esp, dX, dW1, dW2, ws, row_counts=None,
+                       tile=0):
     wp, wb = _ws_args(ws)
     _check(lib().moe_expert_ffn_bwd(_ptr(dY), _ptr(X), _ptr(Z), _ptr(A), _ptr(W1), _ptr(W2), dtype_code(X),
-                                    n_src, G, C, M, H, esp_idx, n_esp, _ptr(row_counts), _ptr(dX), _ptr(dW1), _ptr(dW2),
-                                    wp, wb, _stream()), "moe_expert_ffn_bwd")
+                                    n_src, G, C, M, H, esp_idx, n_esp, _ptr(row_counts), tile, _ptr(dX), _ptr(dW1),
+                                    _ptr(dW2), wp, wb, _stream()), "moe_expert_ffn_bwd")
 
 
 def moe_expert_ffn_bwd_gather(dY, x, inv, S, k, Z, A, W1, W2, E, C, M, H, esp_idx, n_esp, dX, dW1, dW2, ws,
-                              row_counts=None):
+                              row_counts=None, tile=0):
     wp, wb = _ws_args(ws)
     _check(lib().moe_expert_ffn_bwd_gather(_ptr(dY), _ptr(x), S, _ptr(inv), k, _ptr(Z), _ptr(A), _ptr(W1), _ptr(W2),
-                                           dtype_code(x), E, C, M, H, esp_idx, n_esp, _ptr(row_counts), _ptr(dX),
+                                           dtype_code(x), E, C, M, H, esp_idx, n_esp, _ptr(row_counts), tile, _ptr(dX),
                                            _ptr(dW1), _ptr(dW2), wp, wb, _stream()), "moe_expert_ffn_bwd_gather")
 
 

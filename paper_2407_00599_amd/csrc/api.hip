@@ -16,7 +16,7 @@ extern "C" const char* moe_strerror(int err) {
   }
 }
 
-extern "C" int moe_abi_version(void) { return 5; }
+extern "C" int moe_abi_version(void) { return 6; }
 
 // Section II-A: T := k * f * B * L / E, here for the S tokens this rank gates; rounded up.
 extern "C" int64_t moe_capacity(int64_t S, int E, int k, double f) {

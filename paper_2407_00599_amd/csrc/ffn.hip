@@ -15,16 +15,18 @@
 // g at physical row ((r / C) * G + g) * C + r % C, so no permutation pass is needed and only
 // the last row tile of an expert is ragged.
 //
-// bf16 path: MFMA v_mfma_f32_32x32x16_bf16, fp32 accumulation.  Both MFMA operands want 8
-// consecutive k per lane, so LDS tiles are always [row][k] with k contiguous (row pitch 64+8
-// bf16, which makes the 16-byte fragment reads bank-conflict free).  Operands whose memory
-// layout has k as the slow index (W1/W2 in the NN GEMMs, both operands of the TN GEMMs) are
-// transposed in registers (8x8 blocks, v_perm) on their way from global memory to LDS.
-// Global->register loads of tile kt+1 are issued before the MFMAs of tile kt (LDS double
-// buffer, one barrier per k tile).  The MFMA is issued with the operands swapped (D^T = B^T
-// A^T) so that a lane ends up with 4 consecutive output columns and stores 8 bytes.
-// Workgroup ids are remapped so that each XCD (ids are dealt round-robin to the 8 XCDs) works
-// on one contiguous range of tiles and its L2 sees the same weight panels.
+// bf16 path: MFMA v_mfma_f32_32x32x16_bf16, fp32 accumulation, two kernels.
+//   ffn_gemm_dma  (every problem with at least 64 tiles of 256 x 256): global memory goes straight to
+//       LDS (buffer_load ... lds), a ring of five 32 KiB stages of k tile 32, 8 waves; operands whose
+//       memory layout has k as the slow index stay in that layout in LDS and are read with the
+//       transposing LDS load, so no transpose pass exists.  Described in front of gemm_dma_tile.
+//   ffn_gemm_bf16 (small problems, 128 x 128 tiles): global -> registers -> LDS tiles [row][k] with
+//       k contiguous (row pitch 64 + 8 bf16: conflict-free 16-byte fragment reads); operands with k as
+//       the slow index are transposed in registers (8x8 blocks, v_perm) on their way to LDS; the loads
+//       of k tile kt+1 are issued before the MFMAs of tile kt (LDS double buffer, one barrier per tile).
+// Both issue the MFMA with the operands swapped (D^T = B^T A^T) so that a lane ends up with 4
+// consecutive output columns.  Workgroup ids are remapped so that each XCD (ids are dealt round-robin
+// to the 8 XCDs) works on one contiguous range of tiles and its L2 sees the same operand panels.
 //
 // fp32 path: a plain LDS-tiled kernel with fp64 accumulation, for the small fp32 configuration.
 #include <type_traits>
@@ -695,7 +697,8 @@ __device__ __forceinline__ void store_tile_lds(const GemmArgs& p, f32x16_t (&acc
 // ------------------------------------------------------------------------------------------
 // bf16 MFMA kernel with an LDS-DMA pipeline (the fast path for large GEMMs).
 //
-// 256x256 output tile, 4 waves (2x2), 128x128 per wave, k tile 32, four LDS stages of 32 KiB.
+// 256x256 (or 192x256) output tile, 8 waves (2 along the rows x 4 along the columns, two per SIMD: 128x64 or
+// 96x64 per wave), k tile 32, a ring of DSTAGES = 5 LDS stages of 32 KiB (all of a compute unit's LDS).
 // Global memory goes straight to LDS (buffer_load ... lds, 16 bytes per lane, no VGPR staging, no
 // ds_write): a wave instruction fills 1 KiB of consecutive 16-byte slots in lane order, so the
 // tile is stored unpadded and bank conflicts are avoided by permuting WHICH 16-byte chunk of a
@@ -707,10 +710,11 @@ __device__ __forceinline__ void store_tile_lds(const GemmArgs& p, f32x16_t (&acc
 //       chunk c of k-row k sits in slot c ^ (4 (k & 3)); fragments are read with the transposing
 //       LDS load ds_read_b64_tr_b16: a 16-lane group reads a 4(k) x 16(col) patch (lane s: k-row
 //       s/4, 8-byte piece s%4) and lane i receives the 4 k-values of column i.
-// Pipeline: tile t+3 is requested while tile t is multiplied.  Once per k tile, between its two
-// 16-wide MFMA steps, each wave waits until its own requests for tile t+1 have landed
-// (s_waitcnt vmcnt), all waves meet at a barrier, and the stage freed by tile t-1 is refilled.
-// Because the barrier sits in the middle, the first fragments of tile t+1 are fetched under
+// Pipeline: while tile t is multiplied, the B-operand requests of tile t+3 go out during its first
+// 16-wide MFMA step and the A-operand requests of tile t+4 during its second.  Once per k tile, between
+// the two steps, each wave waits until its own requests for tile t+1 have landed (s_waitcnt vmcnt),
+// all waves meet at a barrier, and the stage freed by tile t-1 (the one tile t+4 goes to) may be
+// refilled.  Because the barrier sits in the middle, the first fragments of tile t+1 are fetched under
 // the second MFMA step and no LDS latency is exposed at the tile boundary.
 // ------------------------------------------------------------------------------------------
 #define LDS_AS __attribute__((address_space(3)))
@@ -747,7 +751,8 @@ __device__ __forceinline__ void lds_read_nc(Frag& f, uint32_t addr_lo, uint32_t 
 }
 __device__ __forceinline__ void ready(Frag& f) { asm volatile("" : "+v"(f.q)); }
 
-// WN = waves along n: 2 (4 waves, 128x128 per wave) or 4 (8 waves, 128x64 per wave, two per SIMD).
+// WN = waves along n: 4 (8 waves, 128x64 per wave, two per SIMD) is what is launched; the template also
+// allows 2 (4 waves, 128x128 per wave).
 // TMR = rows of the output tile: 256, or 192 (three 32-row blocks per wave; only for operands A
 // with k contiguous) for problems whose 256-row tiling would leave many compute units idle.
 template <int KIND, int EPI, int WN, int TMR, bool GATHER = false>
@@ -1183,8 +1188,6 @@ __global__ __launch_bounds__(256) void ffn_gemm_f32(const GemmArgs p) {
 // ------------------------------------------------------------------------------------------
 // host side
 // ------------------------------------------------------------------------------------------
-int g_tile_pref = 0;  // 0 auto, 1 = 128x128, 2 = 256x256
-
 int num_cus() {
   static int n = 0;   // same on every device of a node
   if (n == 0) {
@@ -1197,38 +1200,35 @@ int num_cus() {
 }
 
 // Which bf16 kernel and tile a grouped GEMM gets: tile_m x tile_n output tiles; dma = the LDS-DMA
-// kernel (the only one that skips padding rows).
+// kernel (the only one that skips padding rows).  `tile` is the caller's hint (MOE_TILE_*).
 struct TilePlan {
-  bool big, dma;
+  bool dma;
   int tile_m, tile_n;
 };
-TilePlan plan_tiles(bool tn, int G, int Mdim, int Ndim) {
+TilePlan plan_tiles(int tile, bool tn, int G, int Mdim, int Ndim) {
   TilePlan t;
   const int64_t big_tiles = (int64_t)G * ((Mdim + 255) / 256) * ((Ndim + 255) / 256);
-  t.big = big_tiles >= 64;
-  if (g_tile_pref == 1) t.big = false;
-  if (g_tile_pref >= 2) t.big = true;
-  t.tile_n = t.big ? 256 : 128;
+  t.dma = tile == MOE_TILE_AUTO ? big_tiles >= 64 : tile != MOE_TILE_SMALL;
+  t.tile_n = t.dma ? 256 : 128;
   t.tile_m = t.tile_n;
-  t.dma = t.big && (g_tile_pref == 0 || g_tile_pref == 2 || g_tile_pref == 6 || g_tile_pref == 7);
   // 192-row tiles when they need no more rounds of the chip's compute units (weighted by tile height)
-  if (t.big && !tn && (g_tile_pref == 0 || g_tile_pref == 7)) {
+  if (t.dma && !tn && tile != MOE_TILE_256) {
     const int64_t tiles_n = (Ndim + 255) / 256;
     const int64_t t256 = (int64_t)G * ((Mdim + 255) / 256) * tiles_n;
     const int64_t t192 = (int64_t)G * ((Mdim + 191) / 192) * tiles_n;
     const int64_t cu = num_cus();
-    if (g_tile_pref == 7 || ((t192 + cu - 1) / cu) * 192 <= ((t256 + cu - 1) / cu) * 256) t.tile_m = 192;
+    if (tile == MOE_TILE_192 || ((t192 + cu - 1) / cu) * 192 <= ((t256 + cu - 1) / cu) * 256) t.tile_m = 192;
   }
   return t;
 }
 
 // fills the tile counts and buffer sizes of a bf16 problem
-TilePlan prepare_bf16(GemmArgs& a, bool tn) {
+TilePlan prepare_bf16(GemmArgs& a, bool tn, int tile) {
   a.kchunks = (a.Cc + KT - 1) / KT;
   const uint64_t act_rows = (uint64_t)a.n_src * a.G * a.Cc;
   a.a_bytes = (a.gather ? (uint64_t)a.gather_rows : act_rows) * (uint64_t)a.lda * 2;
   a.b_bytes = tn ? act_rows * (uint64_t)a.ldb * 2 : (uint64_t)a.G * (uint64_t)a.b_goff * 2;
-  const TilePlan t = plan_tiles(tn, a.G, a.Mdim, a.Ndim);
+  const TilePlan t = plan_tiles(tile, tn, a.G, a.Mdim, a.Ndim);
   a.tiles_n = (a.Ndim + t.tile_n - 1) / t.tile_n;
   a.tiles_m = (a.Mdim + t.tile_m - 1) / t.tile_m;
   a.total_tiles = a.G * a.tiles_m * a.tiles_n;
@@ -1236,7 +1236,7 @@ TilePlan prepare_bf16(GemmArgs& a, bool tn) {
 }
 
 template <int KIND, int EPI>
-void launch_gemm(GemmArgs a, int dtype, hipStream_t st) {
+void launch_gemm(GemmArgs a, int dtype, int tile, hipStream_t st) {
   if (dtype == MOE_F32) {
     a.tiles_m = (a.Mdim + 63) / 64;
     a.tiles_n = (a.Ndim + 63) / 64;
@@ -1244,21 +1244,20 @@ void launch_gemm(GemmArgs a, int dtype, hipStream_t st) {
     hipLaunchKernelGGL((ffn_gemm_f32<KIND, EPI>), dim3(a.total_tiles), dim3(256), 0, st, a);
     return;
   }
-  const TilePlan t = prepare_bf16(a, KIND == KIND_TN);
+  const TilePlan t = prepare_bf16(a, KIND == KIND_TN, tile);
   const dim3 grid((unsigned)(((a.total_tiles + 7) / 8) * 8));
-  if (t.tile_m == 192) {
+  if (!t.dma) {
+    hipLaunchKernelGGL((ffn_gemm_bf16<128, 128, 2, 2, KIND, EPI>), grid, dim3(256), 0, st, a);
+  } else if (t.tile_m == 192) {
     if constexpr (KIND != KIND_TN) hipLaunchKernelGGL((ffn_gemm_dma<KIND, EPI, 4, 192>), grid, dim3(512), 0, st, a);
-  } else if (t.dma && KIND == KIND_TN && a.gather != nullptr) {
+  } else if (KIND == KIND_TN && a.gather != nullptr) {
     if constexpr (KIND == KIND_TN) hipLaunchKernelGGL((ffn_gemm_dma<KIND, EPI, 4, 256, true>), grid, dim3(512), 0, st, a);
-  } else if (t.dma && g_tile_pref != 2)
+  } else {
     hipLaunchKernelGGL((ffn_gemm_dma<KIND, EPI, 4>), grid, dim3(512), 0, st, a);
-  else if (t.dma)
-    hipLaunchKernelGGL((ffn_gemm_dma<KIND, EPI, 2>), grid, dim3(256), 0, st, a);
-  else if (t.big && g_tile_pref == 3) hipLaunchKernelGGL((ffn_gemm_bf16<256, 256, 2, 4, KIND, EPI>), grid, dim3(512), 0, st, a);
-  else if (t.big && g_tile_pref == 4) hipLaunchKernelGGL((ffn_gemm_bf16<256, 256, 4, 2, KIND, EPI>), grid, dim3(512), 0, st, a);
-  else if (t.big) hipLaunchKernelGGL((ffn_gemm_bf16<256, 256, 2, 2, KIND, EPI>), grid, dim3(256), 0, st, a);
-  else hipLaunchKernelGGL((ffn_gemm_bf16<128, 128, 2, 2, KIND, EPI>), grid, dim3(256), 0, st, a);
+  }
 }
+
+inline bool valid_tile(int tile) { return tile >= MOE_TILE_AUTO && tile <= MOE_TILE_192; }
 
 int check_ffn_shape(int dtype, int n_src, int G, int64_t C, int M, int H, int esp_idx, int n_esp) {
   MOE_REQUIRE(dtype == MOE_F32 || dtype == MOE_BF16, MOE_EINVAL);
@@ -1277,18 +1276,12 @@ int check_ffn_shape(int dtype, int n_src, int G, int64_t C, int M, int H, int es
 
 }  // namespace
 
-extern "C" int moe_ffn_set_tile(int tile) {
-  if (tile < 0 || tile > 7) return MOE_EINVAL;
-  g_tile_pref = tile;
-  return MOE_OK;
-}
-
 // multiplied rows of a row-tiled GEMM (outputs [R rows per expert] x N), or of the reduction of a
 // weight-gradient GEMM, given host-side row counts
-static double rows_multiplied(bool tn, int dtype, int n_src, int G, int64_t C, int Mdim, int Ndim,
+static double rows_multiplied(int tile, bool tn, int dtype, int n_src, int G, int64_t C, int Mdim, int Ndim,
                               const int32_t* cnt) {
   const int64_t R = (int64_t)n_src * C;
-  const TilePlan t = plan_tiles(tn, G, Mdim, Ndim);
+  const TilePlan t = plan_tiles(tile, tn, G, Mdim, Ndim);
   if (cnt == nullptr || dtype != MOE_BF16 || !t.dma) return (double)G * (double)R;
   double rows = 0;
   for (int g = 0; g < G; ++g) {
@@ -1312,17 +1305,17 @@ static double rows_multiplied(bool tn, int dtype, int n_src, int G, int64_t C, i
 }
 
 extern "C" double moe_ffn_executed_flops(int dtype, int n_src, int G, int64_t C, int M, int H, int n_esp,
-                                         const int32_t* row_counts_host, int backward) {
-  if (check_ffn_shape(dtype, n_src, G, C, M, H, 0, n_esp) != MOE_OK) return 0.0;
+                                         const int32_t* row_counts_host, int tile, int backward) {
+  if (check_ffn_shape(dtype, n_src, G, C, M, H, 0, n_esp) != MOE_OK || !valid_tile(tile)) return 0.0;
   const int Hl = H / n_esp;
   const int R = (int)(n_src * C);
   const int32_t* c = row_counts_host;
   const double mh = 2.0 * (double)M * (double)Hl;
   if (!backward)   // Z = X W1 (rows x Hl), Y = A W2 (rows x M)
-    return mh * (rows_multiplied(false, dtype, n_src, G, C, R, Hl, c) + rows_multiplied(false, dtype, n_src, G, C, R, M, c));
+    return mh * (rows_multiplied(tile, false, dtype, n_src, G, C, R, Hl, c) + rows_multiplied(tile, false, dtype, n_src, G, C, R, M, c));
   // dA = dY W2^T (rows x Hl), dW2 (Hl x M over the rows), dW1 (M x Hl over the rows), dX = dZ W1^T (rows x M)
-  return mh * (rows_multiplied(false, dtype, n_src, G, C, R, Hl, c) + rows_multiplied(true, dtype, n_src, G, C, Hl, M, c) +
-               rows_multiplied(true, dtype, n_src, G, C, M, Hl, c) + rows_multiplied(false, dtype, n_src, G, C, R, M, c));
+  return mh * (rows_multiplied(tile, false, dtype, n_src, G, C, R, Hl, c) + rows_multiplied(tile, true, dtype, n_src, G, C, Hl, M, c) +
+               rows_multiplied(tile, true, dtype, n_src, G, C, M, Hl, c) + rows_multiplied(tile, false, dtype, n_src, G, C, R, M, c));
 }
 
 extern "C" size_t moe_ffn_workspace_bytes(int dtype, int n_src, int G, int64_t C, int M, int H, int n_esp) {
@@ -1333,8 +1326,9 @@ extern "C" size_t moe_ffn_workspace_bytes(int dtype, int n_src, int G, int64_t C
 
 static int ffn_fwd_impl(const void* X, const int32_t* gather, int gather_k, int64_t gather_rows, int dtype,
                         const void* W1, const void* W2, int n_src, int G, int64_t C, int M, int H, int esp_idx,
-                        int n_esp, const int32_t* row_counts, void* Z, void* A, void* Y, void* stream) {
+                        int n_esp, const int32_t* row_counts, int tile, void* Z, void* A, void* Y, void* stream) {
   if (int rc = check_ffn_shape(dtype, n_src, G, C, M, H, esp_idx, n_esp)) return rc;
+  MOE_REQUIRE(valid_tile(tile), MOE_EINVAL);
   MOE_REQUIRE_PTR(X); MOE_REQUIRE_PTR(W1); MOE_REQUIRE_PTR(W2); MOE_REQUIRE_PTR(Z); MOE_REQUIRE_PTR(A);
   MOE_REQUIRE_PTR(Y);
   MOE_REQUIRE((((uintptr_t)row_counts) & 3u) == 0, MOE_EALIGN);
@@ -1350,21 +1344,21 @@ static int ffn_fwd_impl(const void* X, const int32_t* gather, int gather_k, int6
   a.B = W1; a.ldb = H; a.b_goff = (int64_t)M * H; a.b_off = h0;
   a.C = Z; a.C2 = A; a.ldc = Hl;
   a.Mdim = a.R; a.Ndim = Hl; a.Kdim = M;
-  launch_gemm<KIND_NN, EPI_GELU>(a, dtype, st);
+  launch_gemm<KIND_NN, EPI_GELU>(a, dtype, tile, st);
   // Y = A * W2[h0:h0+Hl, :]
   a.A = A; a.lda = Hl;
   a.gather = nullptr; a.gather_k = 0; a.gather_rows = 0;
   a.B = W2; a.ldb = M; a.b_goff = (int64_t)H * M; a.b_off = h0 * M;
   a.C = Y; a.C2 = nullptr; a.ldc = M;
   a.Mdim = a.R; a.Ndim = M; a.Kdim = Hl;
-  launch_gemm<KIND_NN, EPI_STORE>(a, dtype, st);
+  launch_gemm<KIND_NN, EPI_STORE>(a, dtype, tile, st);
   return moe::check_launch();
 }
 
 extern "C" int moe_expert_ffn_fwd(const void* X, int dtype, const void* W1, const void* W2, int n_src, int G,
-                                  int64_t C, int M, int H, int esp_idx, int n_esp, const int32_t* row_counts, void* Z,
-                                  void* A, void* Y, void* stream) {
-  return ffn_fwd_impl(X, nullptr, 0, 0, dtype, W1, W2, n_src, G, C, M, H, esp_idx, n_esp, row_counts, Z, A, Y, stream);
+                                  int64_t C, int M, int H, int esp_idx, int n_esp, const int32_t* row_counts, int tile,
+                                  void* Z, void* A, void* Y, void* stream) {
+  return ffn_fwd_impl(X, nullptr, 0, 0, dtype, W1, W2, n_src, G, C, M, H, esp_idx, n_esp, row_counts, tile, Z, A, Y, stream);
 }
 
 // arguments of the fused-dispatch entry points: token matrix [S, M] and the inverse slot map
@@ -1378,16 +1372,17 @@ static int check_gather(const void* x, int dtype, int64_t S, const int32_t* inv,
 
 extern "C" int moe_expert_ffn_fwd_gather(const void* x, int dtype, int64_t S, const int32_t* inv, int k, const void* W1,
                                          const void* W2, int E, int64_t C, int M, int H, int esp_idx, int n_esp,
-                                         const int32_t* row_counts, void* Z, void* A, void* Y, void* stream) {
+                                         const int32_t* row_counts, int tile, void* Z, void* A, void* Y, void* stream) {
   if (int rc = check_gather(x, dtype, S, inv, k, M)) return rc;
-  return ffn_fwd_impl(x, inv, k, S, dtype, W1, W2, 1, E, C, M, H, esp_idx, n_esp, row_counts, Z, A, Y, stream);
+  return ffn_fwd_impl(x, inv, k, S, dtype, W1, W2, 1, E, C, M, H, esp_idx, n_esp, row_counts, tile, Z, A, Y, stream);
 }
 
 static int ffn_bwd_impl(const void* dY, const void* X, const int32_t* gather, int gather_k, int64_t gather_rows,
                         const void* Z, const void* A, const void* W1, const void* W2, int dtype, int n_src, int G,
-                        int64_t C, int M, int H, int esp_idx, int n_esp, const int32_t* row_counts, void* dX, void* dW1,
-                        void* dW2, void* ws, size_t ws_bytes, void* stream) {
+                        int64_t C, int M, int H, int esp_idx, int n_esp, const int32_t* row_counts, int tile, void* dX,
+                        void* dW1, void* dW2, void* ws, size_t ws_bytes, void* stream) {
   if (int rc = check_ffn_shape(dtype, n_src, G, C, M, H, esp_idx, n_esp)) return rc;
+  MOE_REQUIRE(valid_tile(tile), MOE_EINVAL);
   MOE_REQUIRE_PTR(dY); MOE_REQUIRE_PTR(X); MOE_REQUIRE_PTR(Z); MOE_REQUIRE_PTR(A); MOE_REQUIRE_PTR(W1);
   MOE_REQUIRE_PTR(W2); MOE_REQUIRE_PTR(dX); MOE_REQUIRE_PTR(dW1); MOE_REQUIRE_PTR(dW2);
   const size_t need = moe_ffn_workspace_bytes(dtype, n_src, G, C, M, H, n_esp);
@@ -1407,7 +1402,7 @@ static int ffn_bwd_impl(const void* dY, const void* X, const int32_t* gather, in
   a.B = W2; a.ldb = M; a.b_goff = (int64_t)H * M; a.b_off = h0 * M;
   a.C = dZ; a.C2 = nullptr; a.Zin = Z; a.ldc = Hl;
   a.Mdim = a.R; a.Ndim = Hl; a.Kdim = M;
-  launch_gemm<KIND_NT, EPI_DGELU>(a, dtype, st);
+  launch_gemm<KIND_NT, EPI_DGELU>(a, dtype, tile, st);
   // dW2[h0:h0+Hl, :] = Act^T * dY
   GemmArgs w2 = a;
   w2.A = Act; w2.lda = Hl;
@@ -1429,10 +1424,10 @@ static int ffn_bwd_impl(const void* dY, const void* X, const int32_t* gather, in
   dx.B = W1; dx.ldb = H; dx.b_goff = (int64_t)M * H; dx.b_off = h0;
   dx.C = dX; dx.ldc = M; dx.c_goff = 0; dx.c_off = 0;
   dx.Mdim = a.R; dx.Ndim = M; dx.Kdim = Hl;
-  if (dtype == MOE_BF16 && (g_tile_pref == 0 || g_tile_pref == 6 || g_tile_pref == 7)) {
-    // the three are independent: one launch, long row tiles first, if all of them take the 8-wave kernel
+  if (dtype == MOE_BF16) {
+    // the three are independent: one launch, long row tiles first, if all of them take the LDS-DMA kernel
     GemmArgs px = dx, p2 = w2, p1 = w1;
-    const TilePlan tx = prepare_bf16(px, false), t2 = prepare_bf16(p2, true), t1 = prepare_bf16(p1, true);
+    const TilePlan tx = prepare_bf16(px, false, tile), t2 = prepare_bf16(p2, true, tile), t1 = prepare_bf16(p1, true, tile);
     if (tx.dma && t2.dma && t1.dma) {
       const int nbx = (px.total_tiles + 7) / 8 * 8, nb2 = (p2.total_tiles + 7) / 8 * 8, nb1 = (p1.total_tiles + 7) / 8 * 8;
       const dim3 grid((unsigned)(nbx + nb2 + nb1));
@@ -1446,26 +1441,27 @@ static int ffn_bwd_impl(const void* dY, const void* X, const int32_t* gather, in
       return moe::check_launch();
     }
   }
-  launch_gemm<KIND_TN, EPI_STORE>(w2, dtype, st);
-  launch_gemm<KIND_TN, EPI_STORE>(w1, dtype, st);
-  launch_gemm<KIND_NT, EPI_STORE>(dx, dtype, st);
+  launch_gemm<KIND_TN, EPI_STORE>(w2, dtype, tile, st);
+  launch_gemm<KIND_TN, EPI_STORE>(w1, dtype, tile, st);
+  launch_gemm<KIND_NT, EPI_STORE>(dx, dtype, tile, st);
   return moe::check_launch();
 }
 
 extern "C" int moe_expert_ffn_bwd(const void* dY, const void* X, const void* Z, const void* A, const void* W1,
                                   const void* W2, int dtype, int n_src, int G, int64_t C, int M, int H, int esp_idx,
-                                  int n_esp, const int32_t* row_counts, void* dX, void* dW1, void* dW2, void* ws,
-                                  size_t ws_bytes, void* stream) {
-  return ffn_bwd_impl(dY, X, nullptr, 0, 0, Z, A, W1, W2, dtype, n_src, G, C, M, H, esp_idx, n_esp, row_counts, dX, dW1,
-                      dW2, ws, ws_bytes, stream);
+                                  int n_esp, const int32_t* row_counts, int tile, void* dX, void* dW1, void* dW2,
+                                  void* ws, size_t ws_bytes, void* stream) {
+  return ffn_bwd_impl(dY, X, nullptr, 0, 0, Z, A, W1, W2, dtype, n_src, G, C, M, H, esp_idx, n_esp, row_counts, tile, dX,
+                      dW1, dW2, ws, ws_bytes, stream);
 }
 
 extern "C" int moe_expert_ffn_bwd_gather(const void* dY, const void* x, int64_t S, const int32_t* inv, int k,
                                          const void* Z, const void* A, const void* W1, const void* W2, int dtype, int E,
                                          int64_t C, int M, int H, int esp_idx, int n_esp, const int32_t* row_counts,
-                                         void* dX, void* dW1, void* dW2, void* ws, size_t ws_bytes, void* stream) {
+                                         int tile, void* dX, void* dW1, void* dW2, void* ws, size_t ws_bytes,
+                                         void* stream) {
   if (int rc = check_gather(x, dtype, S, inv, k, M)) return rc;
   MOE_REQUIRE((int64_t)E * C <= (1ll << 29), MOE_EUNSUPPORTED);   // 32-bit byte offsets into the slot map
-  return ffn_bwd_impl(dY, x, inv, k, S, Z, A, W1, W2, dtype, 1, E, C, M, H, esp_idx, n_esp, row_counts, dX, dW1, dW2, ws,
-                      ws_bytes, stream);
+  return ffn_bwd_impl(dY, x, inv, k, S, Z, A, W1, W2, dtype, 1, E, C, M, H, esp_idx, n_esp, row_counts, tile, dX, dW1, dW2,
+                      ws, ws_bytes, stream);
 }

@@ -4,8 +4,9 @@
 collectives of Section III (gate -> dispatch -> [AlltoAll] -> expert FFN -> [AlltoAll] ->
 combine, and the mirror image backward).  With all E experts local and the N_ESP shards run
 one after the other on the same GPU it evaluates the whole layer ("closed world"), which is
-what the parity tests compare with the CPU checker.  Nothing is computed here: every step is
-a library call; torch only owns the memory.
+what the parity tests compare with the CPU checker.  Nothing of the method is computed here: every
+step is a library call and torch only owns the memory (MoERankShape.fill_stand_ins copies buffers where a
+collective would move them).
 """
 from __future__ import annotations
 
@@ -101,87 +102,10 @@ class MoERankLayer:
         return self.dx
 
 
-class MoES2Group:
-    """Schedule S2 (Section III-B) for one MP group, evaluated on one GPU: the gate and the combine see
-    all tokens of the group; between them each of the n_mp ranks dispatches, and feeds to the experts,
-    only its slot range of the [E, C, M] buffer (moe_dispatch_slots).  The ranks run one after the
-    other; the copies of their parts into the full buffers stand in for the MP-AllGather (forward and
-    backward), the sum of their weight gradients for the gradient reduction over the group.  All experts
-    are local and the N_ESP shards run in turn, as in MoERankLayer."""
-
-    def __init__(self, S_total, M, H, E, k, f, dtype=torch.bfloat16, n_mp=2, n_esp=1, norm_topk=-1, device="cuda:0"):
-        self.S, self.M, self.H, self.E, self.k, self.f = S_total, M, H, E, k, f
-        self.n_mp, self.n_esp, self.norm_topk = n_mp, n_esp, norm_topk
-        S = S_total
-        self.C = C = api.moe_capacity(S, E, k, f)
-        self.Hl = Hl = H // n_esp
-        self.dt = api.MOE_BF16 if dtype == torch.bfloat16 else api.MOE_F32
-        self.ranges = [((r * C) // n_mp, ((r + 1) * C) // n_mp) for r in range(n_mp)]
-        dev = torch.device(device)
-        i32, f32 = torch.int32, torch.float32
-        e = lambda *shape, dt=dtype: torch.empty(shape, dtype=dt, device=dev)
-        self.logits = e(S, E, dt=f32); self.idx = e(S, k, dt=i32); self.slot = e(S, k, dt=i32)
-        self.w = e(S, k, dt=f32); self.inv = e(E, C, dt=i32); self.counts = e(E, dt=i32)
-        self.parts = [e(E, c1 - c0, M) for c0, c1 in self.ranges]            # each rank's dispatched part
-        self.Z = [e(n_esp, E, c1 - c0, Hl) for c0, c1 in self.ranges]
-        self.A = [e(n_esp, E, c1 - c0, Hl) for c0, c1 in self.ranges]
-        self.Ypart = e(E, C, M)                                              # scratch for one rank's output
-        self.Yret = e(n_esp, E, C, M); self.y = e(S, M)
-        self.dw = e(S, k, dt=f32); self.dYpart = e(E, C, M); self.dXpart = e(E, C, M)
-        self.dbuf = e(n_esp, E, C, M)
-        self.dW1 = e(E, M, H); self.dW2 = e(E, H, M); self.dW1r = e(E, M, H); self.dW2r = e(E, H, M)
-        self.dx = e(S, M); self.dlogits = e(S, E, dt=f32); self.dWg = e(M, E, dt=f32); self.dbias = e(E, dt=f32)
-        cmax = max(c1 - c0 for c0, c1 in self.ranges)
-        nbytes = max(api.moe_gate_workspace_bytes(S, E, k), api.moe_ffn_workspace_bytes(self.dt, 1, E, max(cmax, 1), M, H, n_esp),
-                     api.moe_gate_bwd_workspace_bytes(S, M, E), 256)
-        self.ws = torch.empty(nbytes, dtype=torch.uint8, device=dev)
-
-    def forward(self, x, Wg, bias, W1, W2):
-        S, M, E, k, C, H = self.S, self.M, self.E, self.k, self.C, self.H
-        self.x, self.Wg, self.W1, self.W2 = x, Wg, W1, W2
-        api.moe_gate_topk(x, Wg, bias, S, M, E, k, C, 0, 1, self.norm_topk, self.logits, self.idx, self.slot, self.w,
-                          self.inv, self.counts, self.ws)
-        for r, (c0, c1) in enumerate(self.ranges):
-            if c1 == c0:
-                continue
-            Cr = c1 - c0
-            api.moe_dispatch_slots(x, S, M, E, k, C, c0, c1, self.inv, None, self.parts[r])
-            for j in range(self.n_esp):
-                Y = self.Ypart.view(-1)[:E * Cr * M].view(1, E, Cr, M)
-                api.moe_expert_ffn_fwd(self.parts[r].view(1, E, Cr, M), W1, W2, 1, E, Cr, M, H, j, self.n_esp,
-                                       self.Z[r][j], self.A[r][j], Y)
-                self.Yret[j, :, c0:c1].copy_(Y[0])                           # MP-AllGather
-        api.moe_combine_fwd(self.Yret, self.n_esp, S, M, E, k, C, self.idx, self.slot, self.w, self.y)
-        return self.y
-
-    def backward(self, dy):
-        S, M, E, k, C, H = self.S, self.M, self.E, self.k, self.C, self.H
-        api.moe_combine_bwd(dy, self.Yret, self.n_esp, S, M, E, k, C, self.idx, self.slot, self.inv, self.w, None, self.dw)
-        self.dW1.zero_(); self.dW2.zero_(); self.dbuf.zero_()
-        for r, (c0, c1) in enumerate(self.ranges):
-            if c1 == c0:
-                continue
-            Cr = c1 - c0
-            dYp = self.dYpart.view(-1)[:E * Cr * M].view(1, E, Cr, M)
-            api.moe_dispatch_slots(dy, S, M, E, k, C, c0, c1, self.inv, self.w, dYp)
-            for j in range(self.n_esp):
-                dXp = self.dXpart.view(-1)[:E * Cr * M].view(1, E, Cr, M)
-                api.moe_expert_ffn_bwd(dYp, self.parts[r].view(1, E, Cr, M), self.Z[r][j], self.A[r][j], self.W1, self.W2,
-                                       1, E, Cr, M, H, j, self.n_esp, dXp, self.dW1r, self.dW2r, self.ws)
-                self.dbuf[j, :, c0:c1].copy_(dXp[0])                         # MP-AllGather of the backward pass
-                hs = slice(j * self.Hl, (j + 1) * self.Hl)
-                self.dW1[:, :, hs] += self.dW1r[:, :, hs]                    # gradient reduction over the MP group
-                self.dW2[:, hs, :] += self.dW2r[:, hs, :]
-        api.moe_combine_fwd(self.dbuf, self.n_esp, S, M, E, k, C, self.idx, self.slot, None, self.dx)
-        api.moe_gate_bwd(self.dw, self.w, self.idx, self.logits, self.x, self.Wg, S, M, E, k, self.norm_topk,
-                         self.dlogits, self.dWg, self.dbias, self.dx, 1, self.ws)
-        return self.dx
-
-
 class MoERankShape:
     """One rank's step at its real shapes when the experts are NOT all local (N_EP > 1 or
     N_ESP > 1).  The two EP&ESP-AlltoAlls cannot run on one GPU, so the tensors that would
-    arrive through them are caller-provided stand-ins of the right shape:
+    arrive through them are stand-ins of the right shape (fill_stand_ins builds them from the rank's own data):
         Xrecv  [n_src, G, C, M]    what the first AlltoAll delivers to the local experts
         Yret   [n_esp, E, C, M]    what the second AlltoAll returns (N_ESP partial sums)
         dYrecv [n_src, G, C, M]    backward: gradient rows delivered to the local experts
@@ -191,8 +115,9 @@ class MoERankShape:
     buffers and the step is the complete layer."""
 
     def __init__(self, S_total, M, H, E, k, f, dtype=torch.bfloat16, n_mp=1, mp_idx=0, n_ep=1, n_esp=1,
-                 esp_idx=0, norm_topk=-1, device="cuda:0"):
+                 esp_idx=0, norm_topk=-1, device="cuda:0", tile=0):
         self.S_total, self.M, self.H, self.E, self.k, self.f = S_total, M, H, E, k, f
+        self.tile = tile
         self.n_mp, self.mp_idx, self.n_ep, self.n_esp, self.esp_idx = n_mp, mp_idx, n_ep, n_esp, esp_idx
         self.norm_topk = norm_topk
         self.S = S = S_total // n_mp
@@ -222,7 +147,7 @@ class MoERankShape:
         else:
             self.Xrecv = e(n_src, G, C, M); self.Yret = e(n_esp, E, C, M)
             self.dYrecv = e(n_src, G, C, M); self.dbuf = e(n_esp, E, C, M)
-            self.row_counts = None             # [n_src, G] occupancy that would arrive with the AlltoAll; set by the caller
+            self.row_counts = torch.empty(n_src, G, dtype=i32, device=dev)   # occupancy that would arrive with the AlltoAll
         nbytes = max(api.moe_gate_workspace_bytes(S, E, k),
                      api.moe_ffn_workspace_bytes(self.dt, n_src, G, C, M, H, n_esp),
                      api.moe_gate_bwd_workspace_bytes(S, M, E), 256)
@@ -232,6 +157,28 @@ class MoERankShape:
         S = self.S
         self.x_full, self.x = x_full, x_full[self.mp_idx * S:(self.mp_idx + 1) * S]
         self.Wg, self.bias, self.W1, self.W2, self.dy = Wg, bias, W1, W2, dy
+
+    def fill_stand_ins(self):
+        """Builds, in one pass over the calls, what the collectives would deliver to a rank that does not hold
+        every expert, from the rank's own data (the copies stand in for the AlltoAlls; a peer's tokens are
+        distributed like the rank's own): source chunk s of the expert input, and of the gradient input, is
+        chunk s mod N_EP of the rank's own send buffer, with the gate's demand counts of those experts as its
+        occupancy; the returned buffers are the rank's own expert outputs, chunk for chunk."""
+        assert not self.closed
+        n_ep, G, C, M = self.n_ep, self.G, self.C, self.M
+        self.gate(); self.dispatch()
+        send, cnt = self.buf.view(n_ep, G, C, M), self.counts.view(n_ep, G)
+        for s in range(self.n_src):
+            self.Xrecv[s].copy_(send[s % n_ep]); self.row_counts[s].copy_(cnt[s % n_ep])
+        self.row_counts.clamp_(max=C)
+        self.ffn_fwd()
+        self.Yret.copy_(self.Yout.view(self.n_esp, self.E, C, M))
+        self.combine(); self.combine_bwd()
+        dsend = self.dYret.view(n_ep, G, C, M)
+        for s in range(self.n_src):
+            self.dYrecv[s].copy_(dsend[s % n_ep])
+        self.ffn_bwd()
+        self.dbuf.copy_(self.dXout.view(self.n_esp, self.E, C, M))
 
     # the individual calls, so a benchmark can time them one by one
     def gate(self):
@@ -244,13 +191,14 @@ class MoERankShape:
 
     def ffn_fwd(self):
         api.moe_expert_ffn_fwd(self.Xrecv, self.W1, self.W2, self.n_src, self.G, self.C, self.M, self.H, self.esp_idx,
-                               self.n_esp, self.Z, self.A, self.Yout, self.row_counts)
+                               self.n_esp, self.Z, self.A, self.Yout, self.row_counts, self.tile)
 
     def ffn_fwd_gather(self):
         """dispatch + ffn_fwd in one call (every expert local); not one of STEPS."""
         assert self.closed
         api.moe_expert_ffn_fwd_gather(self.x, self.inv, self.S, self.k, self.W1, self.W2, self.E, self.C, self.M,
-                                      self.H, self.esp_idx, self.n_esp, self.Z, self.A, self.Yout, self.row_counts)
+                                      self.H, self.esp_idx, self.n_esp, self.Z, self.A, self.Yout, self.row_counts,
+                                      self.tile)
 
     def combine(self):
         api.moe_combine_fwd(self.Yret, self.n_esp, self.S, self.M, self.E, self.k, self.C, self.idx, self.slot,
@@ -263,14 +211,14 @@ class MoERankShape:
     def ffn_bwd(self):
         api.moe_expert_ffn_bwd(self.dYrecv, self.Xrecv, self.Z, self.A, self.W1, self.W2, self.n_src, self.G, self.C,
                                self.M, self.H, self.esp_idx, self.n_esp, self.dXout, self.dW1, self.dW2, self.ws,
-                               self.row_counts)
+                               self.row_counts, self.tile)
 
     def ffn_bwd_gather(self):
         """ffn_bwd that reads the rows of X from the token matrix (every expert local); not one of STEPS."""
         assert self.closed
         api.moe_expert_ffn_bwd_gather(self.dYrecv, self.x, self.inv, self.S, self.k, self.Z, self.A, self.W1, self.W2,
                                       self.E, self.C, self.M, self.H, self.esp_idx, self.n_esp, self.dXout, self.dW1,
-                                      self.dW2, self.ws, self.row_counts)
+                                      self.dW2, self.ws, self.row_counts, self.tile)
 
     def dispatch_bwd(self):
         api.moe_combine_fwd(self.dbuf, self.n_esp, self.S, self.M, self.E, self.k, self.C, self.idx, self.slot, None,

@@ -35,7 +35,7 @@ def test_every_declared_symbol_is_exported_and_bound(L):
     for n in names:                       # the Python binding has the same names
         if n not in ("moe_strerror", "moe_abi_version"):
             assert hasattr(api, n), n
-    assert L.moe_abi_version() == 5
+    assert L.moe_abi_version() == 6
 
 
 def test_error_strings(L):
@@ -108,8 +108,8 @@ def test_ffn_argument_checks(L):
     assert f(0, 2, 4, 100, 64, 256, 2) >= 2 * 4 * 100 * 128 * 4
     assert f(1, 2, 4, 100, 64, 250, 4) == 0                 # H % n_esp != 0 -> invalid -> 0
 
-    def fwd(dt=1, n_src=1, G=2, C=10, M=64, H=128, e=0, n=1, X=A, Z=A, Act=A):
-        return L.moe_expert_ffn_fwd(X, dt, A, A, n_src, G, C, M, H, e, n, None, Z, Act, A, None)
+    def fwd(dt=1, n_src=1, G=2, C=10, M=64, H=128, e=0, n=1, X=A, Z=A, Act=A, tile=0):
+        return L.moe_expert_ffn_fwd(X, dt, A, A, n_src, G, C, M, H, e, n, None, tile, Z, Act, A, None)
     assert fwd(H=130, n=4) == -1
     assert fwd(e=2, n=2) == -1
     assert fwd(e=-1) == -1
@@ -120,8 +120,9 @@ def test_ffn_argument_checks(L):
     assert fwd(X=None) == -6
     assert fwd(Z=U) == -3
     assert fwd(Act=None) == -6
+    assert fwd(tile=4) == -1 and fwd(tile=-1) == -1          # unknown tile hint
     def fwd_g(x=A, S=16, inv=A, k=2, E=2, C=10, M=64, H=128, Z=A):
-        return L.moe_expert_ffn_fwd_gather(x, 1, S, inv, k, A, A, E, C, M, H, 0, 1, None, Z, A, A, None)
+        return L.moe_expert_ffn_fwd_gather(x, 1, S, inv, k, A, A, E, C, M, H, 0, 1, None, 0, Z, A, A, None)
     assert fwd_g(k=0) == -1 and fwd_g(k=9) == -1 and fwd_g(S=0) == -1
     assert fwd_g(inv=None) == -6 and fwd_g(x=None) == -6
     assert fwd_g(inv=U) == -3
@@ -130,15 +131,15 @@ def test_ffn_argument_checks(L):
     assert fwd_g(S=(1 << 28) + 1, k=2) == -2 and fwd_g(S=1 << 28, k=2, x=None) == -6
 
     def bwd_g(x=A, S=16, inv=A, k=2, dW1=A, ws=A, wsb=1 << 30):
-        return L.moe_expert_ffn_bwd_gather(A, x, S, inv, k, A, A, A, A, 1, 2, 10, 64, 128, 0, 1, None, A, dW1, A, ws, wsb, None)
+        return L.moe_expert_ffn_bwd_gather(A, x, S, inv, k, A, A, A, A, 1, 2, 10, 64, 128, 0, 1, None, 0, A, dW1, A, ws, wsb, None)
     assert bwd_g(k=0) == -1 and bwd_g(S=0) == -1
     assert bwd_g(inv=None) == -6 and bwd_g(x=U) == -3 and bwd_g(dW1=None) == -6
     assert bwd_g(wsb=64) == -5 and bwd_g(ws=None) == -5
-    assert L.moe_expert_ffn_bwd(A, A, A, A, A, A, 1, 1, 2, 10, 64, 128, 0, 1, None, A, A, None, A, 1 << 30, None) == -6
-    assert L.moe_expert_ffn_bwd(A, A, A, None, A, A, 1, 1, 2, 10, 64, 128, 0, 1, None, A, A, A, A, 1 << 30, None) == -6
-    assert L.moe_expert_ffn_bwd(A, A, A, A, A, A, 1, 1, 2, 10, 64, 128, 0, 1, None, A, A, A, A, 64, None) == -5
-    assert L.moe_expert_ffn_bwd(A, A, A, A, A, A, 1, 1, 2, 10, 64, 128, 0, 1, None, A, A, A, None, 1 << 30, None) == -5
-    assert L.moe_ffn_set_tile(8) == -1 and L.moe_ffn_set_tile(-1) == -1 and L.moe_ffn_set_tile(0) == 0
+    assert L.moe_expert_ffn_bwd(A, A, A, A, A, A, 1, 1, 2, 10, 64, 128, 0, 1, None, 0, A, A, None, A, 1 << 30, None) == -6
+    assert L.moe_expert_ffn_bwd(A, A, A, None, A, A, 1, 1, 2, 10, 64, 128, 0, 1, None, 0, A, A, A, A, 1 << 30, None) == -6
+    assert L.moe_expert_ffn_bwd(A, A, A, A, A, A, 1, 1, 2, 10, 64, 128, 0, 1, None, 0, A, A, A, A, 64, None) == -5
+    assert L.moe_expert_ffn_bwd(A, A, A, A, A, A, 1, 1, 2, 10, 64, 128, 0, 1, None, 0, A, A, A, None, 1 << 30, None) == -5
+    assert L.moe_expert_ffn_bwd(A, A, A, A, A, A, 1, 1, 2, 10, 64, 128, 0, 1, None, 9, A, A, A, A, 1 << 30, None) == -1
 
 
 def test_executed_flops_accounting(L):
@@ -157,19 +158,20 @@ def test_executed_flops_accounting(L):
     assert f(api.MOE_BF16, n_src, G, C, M, H, 1, np.zeros((1, G), np.int32), True) == 0.0
     # one token per expert: one row tile per expert in the row-tiled GEMMs, one row in the reductions
     one = np.ones((1, G), np.int32)
-    api.moe_ffn_set_tile(6)      # 256-row tiles everywhere
-    try:
-        assert f(api.MOE_BF16, n_src, G, C, M, H, 1, one) == 2 * (2.0 * G * 256 * M * H)
-        assert f(api.MOE_BF16, n_src, G, C, M, H, 1, one, True) == 2 * (2.0 * G * 256 * M * H) + 2 * (2.0 * G * 1 * M * H)
-        # counts above the capacity are clamped; a count on a tile edge needs no further tile
-        assert f(api.MOE_BF16, n_src, G, C, M, H, 1, np.full((1, G), C + 7, np.int32), True) == 4 * full
-        assert f(api.MOE_BF16, n_src, G, C, M, H, 1, np.full((1, G), 512, np.int32)) == 2 * (2.0 * G * 512 * M * H)
-        assert f(api.MOE_BF16, n_src, G, C, M, H, 1, np.full((1, G), 513, np.int32)) == 2 * (2.0 * G * 768 * M * H)
-        # several source chunks: the reductions run over all rows, the row tiles follow each chunk's count
-        got = f(api.MOE_BF16, 2, G, 1024, M, H, 1, np.array([[0] * G, [1] * G], np.int32), True)
-        assert got == 2 * (2.0 * G * 256 * M * H) + 2 * (2.0 * G * 2048 * M * H)
-    finally:
-        api.moe_ffn_set_tile(0)
+    t256 = api.MOE_TILE_256      # 256-row tiles everywhere
+    assert f(api.MOE_BF16, n_src, G, C, M, H, 1, one, tile=t256) == 2 * (2.0 * G * 256 * M * H)
+    assert f(api.MOE_BF16, n_src, G, C, M, H, 1, one, True, tile=t256) == 2 * (2.0 * G * 256 * M * H) + 2 * (2.0 * G * 1 * M * H)
+    # counts above the capacity are clamped; a count on a tile edge needs no further tile
+    assert f(api.MOE_BF16, n_src, G, C, M, H, 1, np.full((1, G), C + 7, np.int32), True, tile=t256) == 4 * full
+    assert f(api.MOE_BF16, n_src, G, C, M, H, 1, np.full((1, G), 512, np.int32), tile=t256) == 2 * (2.0 * G * 512 * M * H)
+    assert f(api.MOE_BF16, n_src, G, C, M, H, 1, np.full((1, G), 513, np.int32), tile=t256) == 2 * (2.0 * G * 768 * M * H)
+    # several source chunks: the reductions run over all rows, the row tiles follow each chunk's count
+    got = f(api.MOE_BF16, 2, G, 1024, M, H, 1, np.array([[0] * G, [1] * G], np.int32), True, tile=t256)
+    assert got == 2 * (2.0 * G * 256 * M * H) + 2 * (2.0 * G * 2048 * M * H)
+    # 192-row tiles in the row-tiled GEMMs only; the small kernel never skips; an unknown hint is an invalid call
+    assert f(api.MOE_BF16, n_src, G, C, M, H, 1, one, tile=api.MOE_TILE_192) == 2 * (2.0 * G * 192 * M * H)
+    assert f(api.MOE_BF16, n_src, G, C, M, H, 1, one, tile=api.MOE_TILE_SMALL) == 2 * full
+    assert f(api.MOE_BF16, n_src, G, C, M, H, 1, one, tile=7) == 0.0
 
 
 def test_gate_bwd_argument_checks(L):

@@ -31,11 +31,11 @@ CASES = [
     # S, k, E, C, M, H, n_esp, esp_idx, dtype, tile, fill
     (64, 2, 4, 40, 64, 128, 1, 0, "f32", 0, 1.0),
     (100, 1, 3, 50, 72, 256, 2, 1, "f32", 0, 0.5),
-    (256, 2, 2, 130, 128, 256, 1, 0, "bf16", 1, 1.0),       # 128x128 register-staged kernel
-    (700, 2, 2, 300, 512, 768, 1, 0, "bf16", 6, 1.0),       # 256-row LDS-DMA tiles
-    (700, 2, 3, 230, 264, 1040, 2, 0, "bf16", 7, 0.7),      # 192-row tiles, ESP slice, ragged everything
-    (512, 4, 4, 600, 256, 512, 1, 0, "bf16", 0, 0.4),       # mostly empty slots
-    (9, 8, 8, 20, 136, 520, 1, 0, "bf16", 6, 1.0),          # k = E = 8, few tokens
+    (256, 2, 2, 130, 128, 256, 1, 0, "bf16", api.MOE_TILE_SMALL, 1.0),   # 128x128 register-staged kernel
+    (700, 2, 2, 300, 512, 768, 1, 0, "bf16", api.MOE_TILE_256, 1.0),     # 256-row LDS-DMA tiles
+    (700, 2, 3, 230, 264, 1040, 2, 0, "bf16", api.MOE_TILE_192, 0.7),    # 192-row tiles, ESP slice, ragged everything
+    (512, 4, 4, 600, 256, 512, 1, 0, "bf16", 0, 0.4),                    # mostly empty slots
+    (9, 8, 8, 20, 136, 520, 1, 0, "bf16", api.MOE_TILE_256, 1.0),        # k = E = 8, few tokens
 ]
 
 
@@ -55,14 +55,10 @@ def test_fused_dispatch_forward(S, k, E, C, M, H, n_esp, esp_idx, dtype, tile, f
     Z, A, Y = new(1, E, C, Hl), new(1, E, C, Hl), new(1, E, C, M)
     Z2, A2, Y2 = new(1, E, C, Hl), new(1, E, C, Hl), new(1, E, C, M)
     buf = new(E, C, M)
-    api.moe_ffn_set_tile(tile)
-    try:
-        api.moe_expert_ffn_fwd_gather(xd, invd, S, k, W1d, W2d, E, C, M, H, esp_idx, n_esp, Z, A, Y, cnt)
-        api.moe_dispatch(xd, S, M, E, k, C, invd, None, buf)
-        api.moe_expert_ffn_fwd(buf, W1d, W2d, 1, E, C, M, H, esp_idx, n_esp, Z2, A2, Y2, cnt)
-        torch.cuda.synchronize()
-    finally:
-        api.moe_ffn_set_tile(0)
+    api.moe_expert_ffn_fwd_gather(xd, invd, S, k, W1d, W2d, E, C, M, H, esp_idx, n_esp, Z, A, Y, cnt, tile)
+    api.moe_dispatch(xd, S, M, E, k, C, invd, None, buf)
+    api.moe_expert_ffn_fwd(buf, W1d, W2d, 1, E, C, M, H, esp_idx, n_esp, Z2, A2, Y2, cnt, tile)
+    torch.cuda.synchronize()
     # the definition: slot (e, c) holds token inv // k, or nothing
     X = O.dispatch(x.val, inv, k)[None]
     rZ, rY = O.expert_ffn_fwd(X, W1.val, W2.val, esp_idx, n_esp)
@@ -83,21 +79,17 @@ def test_fused_dispatch_forward(S, k, E, C, M, H, n_esp, esp_idx, dtype, tile, f
     dt = api.MOE_BF16 if dtype == "bf16" else api.MOE_F32
     ws = torch.empty(api.moe_ffn_workspace_bytes(dt, 1, E, C, M, H, n_esp), dtype=torch.uint8, device=DEV)
     outs = []
-    api.moe_ffn_set_tile(tile)
-    try:
-        for fused in (True, False):
-            dX = new(1, E, C, M); dW1 = torch.full((E, M, H), 3.0, dtype=tdt, device=DEV)
-            dW2 = torch.full((E, H, M), 3.0, dtype=tdt, device=DEV)
-            if fused:
-                api.moe_expert_ffn_bwd_gather(dYd, xd, invd, S, k, Z, A, W1d, W2d, E, C, M, H, esp_idx, n_esp, dX, dW1,
-                                              dW2, ws, cnt)
-            else:
-                api.moe_expert_ffn_bwd(dYd, buf.view(1, E, C, M), Z2, A2, W1d, W2d, 1, E, C, M, H, esp_idx, n_esp, dX,
-                                       dW1, dW2, ws, cnt)
-            torch.cuda.synchronize()
-            outs.append((dX, dW1, dW2))
-    finally:
-        api.moe_ffn_set_tile(0)
+    for fused in (True, False):
+        dX = new(1, E, C, M); dW1 = torch.full((E, M, H), 3.0, dtype=tdt, device=DEV)
+        dW2 = torch.full((E, H, M), 3.0, dtype=tdt, device=DEV)
+        if fused:
+            api.moe_expert_ffn_bwd_gather(dYd, xd, invd, S, k, Z, A, W1d, W2d, E, C, M, H, esp_idx, n_esp, dX, dW1,
+                                          dW2, ws, cnt, tile)
+        else:
+            api.moe_expert_ffn_bwd(dYd, buf.view(1, E, C, M), Z2, A2, W1d, W2d, 1, E, C, M, H, esp_idx, n_esp, dX,
+                                   dW1, dW2, ws, cnt, tile)
+        torch.cuda.synchronize()
+        outs.append((dX, dW1, dW2))
     for a, b in zip(*outs):
         assert torch.equal(a, b)
     rdX, rdW1, rdW2 = O.expert_ffn_bwd(dY.val, X, W1.val, W2.val, esp_idx, n_esp)

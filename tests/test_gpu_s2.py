@@ -7,7 +7,7 @@ import torch
 
 from oracle import moe_oracle as O
 from paper_2407_00599_amd import api, synth
-from paper_2407_00599_amd.layer import MoES2Group
+from s2_group import MoES2Group
 from util import DEV, TOL, to_dev, to_host, rel_err, torch_dtype
 
 pytestmark = pytest.mark.gpu
