@@ -54,7 +54,8 @@ enum {
   MOE_EALIGN = -3,       /* a pointer is not 16-byte aligned */
   MOE_ELAUNCH = -4,      /* HIP reported an error when enqueuing */
   MOE_EWORKSPACE = -5,   /* ws is NULL or ws_bytes is too small */
-  MOE_ENULL = -6         /* a required pointer is NULL */
+  MOE_ENULL = -6,        /* a required pointer is NULL */
+  MOE_ESCRATCH = -7      /* the problem needs more scratch than the library's static array holds */
 };
 
 /* Human-readable name of an error code (static storage, never NULL). */
@@ -96,6 +97,22 @@ int moe_gate_topk(const void* x, int x_dtype, const float* Wg, const float* gate
                   float* logits, int32_t* idx, int32_t* slot, float* w,
                   int32_t* inv, int32_t* counts,
                   void* ws, size_t ws_bytes, void* stream);
+
+/* moe_gate_topk for callers that cannot allocate: code under HIP graph capture, tight serving loops,
+ * harnesses that forbid hipMalloc.  Same arguments, results and errors as moe_gate_topk, minus the
+ * workspace: the per-block histograms live in a static device array of MOE_GATE_STATIC_SCRATCH_BYTES that
+ * every GPU the library runs on holds until the process ends.  The call allocates nothing and frees nothing
+ * (the first call on a device looks the array's address up, once).  A problem whose
+ * moe_gate_workspace_bytes(S, E, k) exceeds the array is rejected with MOE_ESCRATCH (the array covers
+ * ceil(S / 64) * k * E <= 262144, e.g. 32768 tokens x top-2 x 256 experts).  Nothing in the array has to
+ * start at zero (every word a call reads was written by that call), so it needs no clearing; it is shared by
+ * all calls on that GPU: calls that overlap in time on one GPU (different streams or threads) race. */
+#define MOE_GATE_STATIC_SCRATCH_BYTES (2u << 20)
+int moe_gate_topk_static(const void* x, int x_dtype, const float* Wg, const float* gate_bias,
+                         int64_t S_total, int M, int E, int k, int64_t C,
+                         int mp_idx, int n_mp, int norm_topk,
+                         float* logits, int32_t* idx, int32_t* slot, float* w,
+                         int32_t* inv, int32_t* counts, void* stream);
 
 /* ---------------------------------------------------------------------------------------
  * Dispatch: Section II-A defines G in R^{E x T x M}, whose slice G[i,:,:] holds the tokens that

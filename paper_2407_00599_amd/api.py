@@ -15,6 +15,7 @@ import torch
 
 MOE_F32, MOE_BF16 = 0, 1
 MOE_TILE_AUTO, MOE_TILE_SMALL, MOE_TILE_256, MOE_TILE_192 = 0, 1, 2, 3
+MOE_GATE_STATIC_SCRATCH_BYTES = 2 << 20
 _PKG = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_PKG, "libparm_moe.so")
 
@@ -47,6 +48,9 @@ def lib() -> ctypes.CDLL:
         L.moe_gate_topk.restype = c_i
         L.moe_gate_topk.argtypes = [c_p, c_i, c_p, c_p, c_i64, c_i, c_i, c_i, c_i64, c_i, c_i, c_i,
                                     c_p, c_p, c_p, c_p, c_p, c_p, c_p, c_sz, c_p]
+        L.moe_gate_topk_static.restype = c_i
+        L.moe_gate_topk_static.argtypes = [c_p, c_i, c_p, c_p, c_i64, c_i, c_i, c_i, c_i64, c_i, c_i, c_i,
+                                           c_p, c_p, c_p, c_p, c_p, c_p, c_p]
         L.moe_dispatch.restype = c_i
         L.moe_dispatch.argtypes = [c_p, c_i, c_i64, c_i, c_i, c_i, c_i64, c_p, c_p, c_p, c_p]
         L.moe_ffn_workspace_bytes.restype = c_sz
@@ -88,6 +92,7 @@ def lib() -> ctypes.CDLL:
 
 EXPORTED = [
     "moe_strerror", "moe_abi_version", "moe_capacity", "moe_gate_workspace_bytes", "moe_gate_topk",
+    "moe_gate_topk_static",
     "moe_dispatch", "moe_dispatch_slots", "moe_ffn_workspace_bytes", "moe_ffn_executed_flops", "moe_expert_ffn_fwd", "moe_expert_ffn_fwd_gather",
     "moe_expert_ffn_bwd", "moe_expert_ffn_bwd_gather",
     "moe_combine_fwd", "moe_combine_bwd", "moe_gate_bwd_workspace_bytes", "moe_gate_bwd", "moe_alpha_beta_fit",
@@ -154,6 +159,14 @@ def moe_gate_topk(x, Wg, gate_bias, S_total, M, E, k, C, mp_idx, n_mp, norm_topk
                                S_total, M, E, k, C, mp_idx, n_mp, norm_topk,
                                _ptr(logits), _ptr(idx), _ptr(slot), _ptr(w), _ptr(inv), _ptr(counts),
                                wp, wb, _stream()), "moe_gate_topk")
+
+
+def moe_gate_topk_static(x, Wg, gate_bias, S_total, M, E, k, C, mp_idx, n_mp, norm_topk,
+                         logits, idx, slot, w, inv, counts):
+    _check(lib().moe_gate_topk_static(_ptr(x), dtype_code(x) if x is not None else MOE_F32, _ptr(Wg), _ptr(gate_bias),
+                                      S_total, M, E, k, C, mp_idx, n_mp, norm_topk,
+                                      _ptr(logits), _ptr(idx), _ptr(slot), _ptr(w), _ptr(inv), _ptr(counts),
+                                      _stream()), "moe_gate_topk_static")
 
 
 def moe_dispatch(x, S, M, E, k, C, inv, w, buf):

@@ -12,6 +12,7 @@ extern "C" const char* moe_strerror(int err) {
     case MOE_ELAUNCH: return "HIP reported an error while enqueuing";
     case MOE_EWORKSPACE: return "workspace missing or too small";
     case MOE_ENULL: return "required pointer is NULL";
+    case MOE_ESCRATCH: return "problem exceeds the library's static scratch array";
     default: return "unknown error code";
   }
 }

@@ -17,7 +17,14 @@
 //                         slot = base + rank if < C; inverse map; -1 tails of inv.
 // The logits are accumulated in fp64 and rounded once to fp32, so the routing decision is
 // taken on the same fp32 numbers a double-precision reference produces.
+#include <mutex>
+
 #include "common.h"
+
+// Scratch of moe_gate_topk_static: the per-block histograms and their scan, which moe_gate_topk keeps in
+// the caller's workspace.  One copy per GPU, held until the process ends.  In host code this name is only a
+// handle for hipGetSymbolAddress; kernels are given the address that call returns for the current device.
+static __device__ __align__(256) unsigned char scratch[MOE_GATE_STATIC_SCRATCH_BYTES];
 
 namespace {
 
@@ -480,16 +487,34 @@ void launch_topk(const float* logits, int64_t S, int E, int k, int norm, int32_t
 
 }  // namespace
 
+// Address of the current device's copy of the scratch array, looked up once per device (with that device
+// current) and kept; nullptr if the runtime refuses.
+static void* static_scratch() {
+  constexpr int MAX_DEV = 64;
+  static void* ptr[MAX_DEV] = {};
+  static std::mutex mu;
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= MAX_DEV) return nullptr;
+  std::lock_guard<std::mutex> lock(mu);
+  if (ptr[dev] == nullptr) {
+    void* p = nullptr;
+    if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess) return nullptr;
+    ptr[dev] = p;
+  }
+  return ptr[dev];
+}
+
 extern "C" size_t moe_gate_workspace_bytes(int64_t S, int E, int k) {
   if (S < 1 || E < 1 || k < 1) return 0;
   const int64_t nblk = (S + GATE_TB - 1) / GATE_TB;
   return moe::align_up((size_t)nblk * k * E * sizeof(int32_t), 256) * 2;
 }
 
-extern "C" int moe_gate_topk(const void* x, int x_dtype, const float* Wg, const float* gate_bias,
-                             int64_t S_total, int M, int E, int k, int64_t C, int mp_idx, int n_mp, int norm_topk,
-                             float* logits, int32_t* idx, int32_t* slot, float* w, int32_t* inv, int32_t* counts,
-                             void* ws, size_t ws_bytes, void* stream) {
+// ws == nullptr: the workspace is this GPU's static scratch array (moe_gate_topk_static)
+static int gate_topk_impl(const void* x, int x_dtype, const float* Wg, const float* gate_bias,
+                          int64_t S_total, int M, int E, int k, int64_t C, int mp_idx, int n_mp, int norm_topk,
+                          float* logits, int32_t* idx, int32_t* slot, float* w, int32_t* inv, int32_t* counts,
+                          void* ws, size_t ws_bytes, bool static_ws, void* stream) {
   MOE_REQUIRE(n_mp >= 1 && mp_idx >= 0 && mp_idx < n_mp, MOE_EINVAL);
   MOE_REQUIRE(S_total >= 1 && S_total % n_mp == 0, MOE_EINVAL);
   const int64_t S = S_total / n_mp;
@@ -504,8 +529,14 @@ extern "C" int moe_gate_topk(const void* x, int x_dtype, const float* Wg, const 
   MOE_REQUIRE_PTR(logits); MOE_REQUIRE_PTR(idx); MOE_REQUIRE_PTR(slot); MOE_REQUIRE_PTR(w);
   MOE_REQUIRE_PTR(inv); MOE_REQUIRE_PTR(counts);
   const size_t need = moe_gate_workspace_bytes(S, E, k);
-  MOE_REQUIRE(ws != nullptr && ws_bytes >= need, MOE_EWORKSPACE);
-  MOE_REQUIRE(moe::aligned16(ws), MOE_EALIGN);
+  if (static_ws) {
+    MOE_REQUIRE(need <= MOE_GATE_STATIC_SCRATCH_BYTES, MOE_ESCRATCH);
+    ws = static_scratch();
+    MOE_REQUIRE(ws != nullptr, MOE_ELAUNCH);
+  } else {
+    MOE_REQUIRE(ws != nullptr && ws_bytes >= need, MOE_EWORKSPACE);
+    MOE_REQUIRE(moe::aligned16(ws), MOE_EALIGN);
+  }
   const int norm = norm_topk < 0 ? (k >= 2 ? 1 : 0) : norm_topk;
   hipStream_t st = (hipStream_t)stream;
   const int nblk = (int)((S + GATE_TB - 1) / GATE_TB);
@@ -550,4 +581,20 @@ extern "C" int moe_gate_topk(const void* x, int x_dtype, const float* Wg, const 
     hipLaunchKernelGGL(gate_slots<false>, dim3(nblk), dim3(GATE_TB), 0, st, idx, blockbase, counts, S, E, k, C, slot, inv);
   }
   return moe::check_launch();
+}
+
+extern "C" int moe_gate_topk(const void* x, int x_dtype, const float* Wg, const float* gate_bias,
+                             int64_t S_total, int M, int E, int k, int64_t C, int mp_idx, int n_mp, int norm_topk,
+                             float* logits, int32_t* idx, int32_t* slot, float* w, int32_t* inv, int32_t* counts,
+                             void* ws, size_t ws_bytes, void* stream) {
+  return gate_topk_impl(x, x_dtype, Wg, gate_bias, S_total, M, E, k, C, mp_idx, n_mp, norm_topk, logits, idx, slot, w,
+                        inv, counts, ws, ws_bytes, false, stream);
+}
+
+extern "C" int moe_gate_topk_static(const void* x, int x_dtype, const float* Wg, const float* gate_bias,
+                                    int64_t S_total, int M, int E, int k, int64_t C, int mp_idx, int n_mp,
+                                    int norm_topk, float* logits, int32_t* idx, int32_t* slot, float* w,
+                                    int32_t* inv, int32_t* counts, void* stream) {
+  return gate_topk_impl(x, x_dtype, Wg, gate_bias, S_total, M, E, k, C, mp_idx, n_mp, norm_topk, logits, idx, slot, w,
+                        inv, counts, nullptr, 0, true, stream);
 }

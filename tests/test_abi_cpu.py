@@ -87,6 +87,13 @@ def test_gate_argument_checks(L):
     assert call(x=U) == -3
     assert call(wsb=ws - 1) == -5
     assert call(ws=None) == -5
+    # the variant with the library's static scratch array: same checks, and a size limit instead of a workspace
+    def call_static(S=256, E=8, k=2, lg=A):
+        return L.moe_gate_topk_static(A, 1, A, None, S, 64, E, k, 10, 0, 1, -1, lg, A, A, A, A, A, None)
+    assert call_static(k=9) == -1 and call_static(lg=None) == -6 and call_static(lg=U) == -3
+    assert L.moe_gate_workspace_bytes(1 << 20, 256, 8) > api.MOE_GATE_STATIC_SCRATCH_BYTES
+    assert call_static(S=1 << 20, E=256, k=8) == -7
+    assert b"static" in L.moe_strerror(-7)
 
 
 def test_dispatch_combine_argument_checks(L):
