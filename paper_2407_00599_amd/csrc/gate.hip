@@ -18,6 +18,7 @@
 // The logits are accumulated in fp64 and rounded once to fp32, so the routing decision is
 // taken on the same fp32 numbers a double-precision reference produces.
 #include <mutex>
+#include <type_traits>
 
 #include "common.h"
 
@@ -247,6 +248,204 @@ __global__ __launch_bounds__(256) void gate_logits_mfma(const void* __restrict__
     for (int r = 0; r < 4; ++r) {
       const int64_t t = tb + wave * 16 + 4 * r + (lane >> 4);
       if (t < S) logits[t * E + e] = (float)(acc[j][r] + bj);
+    }
+  }
+}
+
+// E <= 16 and many tokens: the fp64 matrix cores in their 4-block form.  v_mfma_f64_4x4x4_4b_f64 multiplies
+// four independent 4 x 4 tiles by 4 x 4 tiles (k = 4) per instruction: lane l = 16 kk + 4 blk + i supplies
+// A_blk[i][kk] and B_blk[kk][i], and receives D_blk[l / 16][l % 4] for blk = (l / 4) % 4 (layout confirmed with
+// a one-wave probe).  On this chip the instruction runs on the fp64 vector units at their FMA rate (16
+// cycles, during which the SIMD issues no other vector instruction), so what it buys is not arithmetic
+// rate but structure: no cross-lane reduction, and every converted x value feeds 4 experts per
+// instruction.  The conversion bf16 -> fp64 costs 20 cycles per 64 values (v_cvt_f64_f32 is quarter rate),
+// as much as 1.25 matrix instructions, so each value is converted exactly once per wave: the four blocks are
+// four token groups (16 tokens per instruction) and the experts are taken in NP passes of 4 that share the
+// converted A operand (NP = 1, 2, 4 for E <= 4, 8, 16).
+//   x:  fetched with whole-line requests (a lane takes 16 bytes, eight consecutive lanes one 128-byte piece
+//       of a token row = 64 m, one instruction 8 rows) three steps ahead into registers, then passed through
+//       a wave-private LDS region to reach the operand layout, in which neighbouring lanes hold DIFFERENT
+//       tokens.  A lane of the operand layout reads 16 bytes = 8 consecutive m of its token, which feed 8
+//       instructions per pass (the k index of instruction s is m = base + 8 kk + s: any bijection between
+//       lanes and m serves, as long as A and B agree); a 64-m step is two such groups.  Row r stores piece p at
+//       slot p ^ r, which makes both the row-wise writes and the operand-layout reads conflict-free.
+//   Wg: converted to fp64 once per block and 512-m super-chunk on its way into LDS (double-buffered, one
+//       barrier per super-chunk), in the order the lanes read it (16 bytes per lane; the four blocks read the
+//       same addresses).
+//   A block is TW x 2 waves: TW token waves (32 tokens each, two accumulator sets per pass), times 2 waves
+//   that split the steps of a super-chunk and add their sums through LDS at the end.
+//   Token rows and weights are fetched through buffer descriptors: an index outside the problem becomes an
+//   out-of-range offset, which the hardware answers with zeros, so the loop body has no branches and the
+//   compiler is free to interleave fetches, conversions and matrix instructions.
+typedef unsigned int g4_u32x4_t __attribute__((ext_vector_type(4)));
+constexpr uint32_t G4_OOB = 0xFFFFFFF0u;
+constexpr int G4_KW = 2, G4_NS = 2, G4_SB = 4, G4_TS = 16;
+constexpr int G4_SC = 64 * G4_SB * G4_KW;    // m per super-chunk
+template <int NP, int TW>
+__global__ __launch_bounds__(64 * TW * G4_KW) void gate_logits_mfma4(const bf16_t* __restrict__ x, const float* __restrict__ Wg,
+                                                                      const float* __restrict__ bias, float* __restrict__ logits,
+                                                                      int64_t S, int M, int E) {
+  constexpr int KW = G4_KW, NS = G4_NS, SB = G4_SB, SC = G4_SC, TS = G4_TS;
+  constexpr int NT = 64 * TW * KW;
+  constexpr int ROWS = NS * TS;        // tokens per wave
+  constexpr int NLD = ROWS / 8;        // fetches per step (8 rows each)
+  constexpr int EP = 4 * NP;           // experts, padded
+  constexpr int STEP_D = 64 * EP;      // doubles per 64-m step: [u 2][pass NP][p 4][kk 4][j 4][2]
+  constexpr int BUF_D = SB * KW * STEP_D;
+  constexpr int NST = SC * EP / NT;    // staged weights per thread and super-chunk
+  static_assert(SC * EP % NT == 0, "staging layout");
+  constexpr int RED_D = TW * KW * NS * NP * 64;
+  __shared__ __attribute__((aligned(16))) double Bs[(2 * BUF_D > RED_D ? 2 * BUF_D : RED_D)];
+  __shared__ __attribute__((aligned(16))) char Xs[TW * KW * ROWS * 128];
+
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int tw = wave / KW, kw = wave % KW;
+  const int kk = lane >> 4, blk = (lane >> 2) & 3, li = lane & 3;
+  const int tok_in_set = 4 * blk + li;
+  const int64_t tset0 = ((int64_t)blockIdx.x * TW + tw) * ROWS;   // first token of this wave
+  const int nsc = (M + SC - 1) / SC;
+
+  // descriptors over the rank's token rows [S, M] and over Wg [M, E] (the host checks both are below 4 GiB)
+  const __amdgpu_buffer_rsrc_t rx = __builtin_amdgcn_make_buffer_rsrc(const_cast<bf16_t*>(x), 0, (uint32_t)((uint64_t)S * M * 2), 0x00020000);
+  const __amdgpu_buffer_rsrc_t rw = __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(Wg), 0, (uint32_t)((uint64_t)M * E * 4), 0x00020000);
+
+  // ---- weights: global -> registers -> fp64 in LDS, in the lanes' read order ----
+  // thread tid stages expert e = tid % EP of the rows ml0 + n (NT / EP), n = 0 .. NST - 1, of a super-chunk
+  float wreg[NST];
+  const int w_e = tid % EP, w_ml0 = tid / EP;
+  const uint32_t w_step = (uint32_t)(NT / EP) * (uint32_t)E * 4u;
+  auto fetch_w = [&](int sc) {
+    const int m_first = sc * SC + w_ml0;
+    const uint32_t base = ((uint32_t)m_first * (uint32_t)E + (uint32_t)w_e) * 4u;
+#pragma unroll
+    for (int n = 0; n < NST; ++n) {
+      const bool ok = (m_first + n * (NT / EP) < M) & (w_e < E);
+      const uint32_t off = ok ? base + (uint32_t)n * w_step : G4_OOB;
+      wreg[n] = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(rw, (int)off, 0, 0));
+    }
+  };
+  auto stage_w = [&](int buf) {
+    double* dst = Bs + buf * BUF_D;
+#pragma unroll
+    for (int n = 0; n < NST; ++n) {
+      const int idx = tid + n * NT, ml = idx / EP, e = idx % EP;
+      const int st = ml >> 6, r = ml & 63, u = r >> 5, k4 = (r & 31) >> 3, sx = r & 7;   // group u = the 32-m half
+      const int ps = e >> 2, j = e & 3;
+      dst[st * STEP_D + ((((u * NP + ps) * 4 + (sx >> 1)) * 4 + k4) * 4 + j) * 2 + (sx & 1)] = (double)wreg[n];
+    }
+  };
+
+  // ---- token rows: ring of SB register sets in the fetch layout (row = lane / 8, 16-byte piece = lane % 8) ----
+  uint4 raw[SB][NLD];
+  uint32_t row_off[NLD];                     // byte offset of this lane's piece at m = 0, or out of range
+#pragma unroll
+  for (int ld = 0; ld < NLD; ++ld) {
+    const int64_t t = tset0 + 8 * ld + (lane >> 3);
+    row_off[ld] = t < S ? (uint32_t)(((uint64_t)t * M + 8 * (lane & 7)) * 2) : G4_OOB;
+  }
+  auto fetch_x = [&](int n, int slot) {      // n = this wave's step number: super-chunk n / SB, step kw SB + n % SB
+    const int m0 = (n / SB) * SC + (kw * SB + n % SB) * 64;
+    const bool in = m0 + 8 * (lane & 7) < M;
+#pragma unroll
+    for (int ld = 0; ld < NLD; ++ld) {
+      const uint32_t off = (row_off[ld] != G4_OOB && in) ? row_off[ld] + (uint32_t)m0 * 2u : G4_OOB;
+      const g4_u32x4_t v = __builtin_amdgcn_raw_buffer_load_b128(rx, (int)off, 0, 0);
+      raw[slot][ld] = make_uint4(v.x, v.y, v.z, v.w);
+    }
+  };
+  // wave-private LDS region [ROWS][8 pieces of 16 bytes], piece p of row r at slot p ^ (r % 8)
+  char* xw = Xs + wave * (ROWS * 128);
+  const int wr_off = (lane >> 3) * 128 + (((lane & 7) ^ (lane >> 3)) * 16);        // + ld * 1024
+  int rd_off[NS][2];                                                              // set q, group u
+#pragma unroll
+  for (int q = 0; q < NS; ++q)
+#pragma unroll
+    for (int u = 0; u < 2; ++u) {
+      const int r = q * TS + tok_in_set;
+      rd_off[q][u] = r * 128 + (((4 * u + kk) ^ (r & 7)) * 16);
+    }
+  const int b_off = (kk * 4 + li) * 2;       // this lane's place among the 16 B lanes of a pass (doubles)
+
+  double acc[NS][NP];
+#pragma unroll
+  for (int q = 0; q < NS; ++q)
+#pragma unroll
+    for (int ps = 0; ps < NP; ++ps) acc[q][ps] = 0.0;
+
+  fetch_w(0);
+  const int nsteps = nsc * SB;
+#pragma unroll
+  for (int n = 0; n < SB - 1; ++n) fetch_x(n, n);
+  stage_w(0);
+  __syncthreads();
+
+  for (int sc = 0; sc < nsc; ++sc) {
+    if (sc + 1 < nsc) fetch_w(sc + 1);
+    const double* bbuf = Bs + (sc & 1) * BUF_D + kw * SB * STEP_D + b_off;
+#pragma unroll
+    for (int sb = 0; sb < SB; ++sb) {
+      const int n = sc * SB + sb;
+      if (n + SB - 1 < nsteps) fetch_x(n + SB - 1, (sb + SB - 1) % SB);
+      // fetch layout -> operand layout through the wave's LDS region (LDS operations of a wave complete in order)
+#pragma unroll
+      for (int ld = 0; ld < NLD; ++ld) *reinterpret_cast<uint4*>(xw + ld * 1024 + wr_off) = raw[sb][ld];
+#pragma unroll
+      for (int u = 0; u < 2; ++u) {
+        double da[NS][8];                    // the 8 values of this lane's piece, converted once
+#pragma unroll
+        for (int q = 0; q < NS; ++q) {
+          const uint4 v = *reinterpret_cast<const uint4*>(xw + rd_off[q][u]);
+#pragma unroll
+          for (int sx = 0; sx < 8; ++sx) {
+            const uint32_t wd = (&v.x)[sx >> 1];
+            da[q][sx] = (double)__uint_as_float((sx & 1) ? (wd & 0xFFFF0000u) : (wd << 16));
+          }
+        }
+#pragma unroll
+        for (int p = 0; p < 4; ++p) {
+          double2 b2[NP];
+#pragma unroll
+          for (int ps = 0; ps < NP; ++ps)
+            b2[ps] = *reinterpret_cast<const double2*>(bbuf + sb * STEP_D + ((u * NP + ps) * 4 + p) * 32);
+#pragma unroll
+          for (int ps = 0; ps < NP; ++ps)
+#pragma unroll
+            for (int q = 0; q < NS; ++q) acc[q][ps] = __builtin_amdgcn_mfma_f64_4x4x4f64(da[q][2 * p], b2[ps].x, acc[q][ps], 0, 0, 0);
+#pragma unroll
+          for (int ps = 0; ps < NP; ++ps)
+#pragma unroll
+            for (int q = 0; q < NS; ++q) acc[q][ps] = __builtin_amdgcn_mfma_f64_4x4x4f64(da[q][2 * p + 1], b2[ps].y, acc[q][ps], 0, 0, 0);
+        }
+      }
+    }
+    if (sc + 1 < nsc) stage_w((sc + 1) & 1);
+    __syncthreads();
+  }
+
+  // ---- add the KW partial sums through LDS (the weight buffers are free now) and store ----
+  double* red = Bs;
+  if (kw != 0) {
+#pragma unroll
+    for (int q = 0; q < NS; ++q)
+#pragma unroll
+      for (int ps = 0; ps < NP; ++ps) red[(((tw * KW + kw) * NS + q) * NP + ps) * 64 + lane] = acc[q][ps];
+  }
+  __syncthreads();
+  if (kw == 0) {
+    const int i = lane >> 4, j = lane & 3;
+#pragma unroll
+    for (int ps = 0; ps < NP; ++ps) {
+      const int e = 4 * ps + j;
+      const double bj = (bias != nullptr && e < E) ? (double)bias[e] : 0.0;
+#pragma unroll
+      for (int q = 0; q < NS; ++q) {
+        double v = acc[q][ps];
+#pragma unroll
+        for (int w2 = 1; w2 < KW; ++w2) v += red[(((tw * KW + w2) * NS + q) * NP + ps) * 64 + lane];
+        const int64_t t = tset0 + q * TS + 4 * blk + i;
+        if (t < S && e < E) logits[t * E + e] = (float)(v + bj);
+      }
     }
   }
 }
@@ -547,7 +746,19 @@ static int gate_topk_impl(const void* x, int x_dtype, const float* Wg, const flo
     const bool bf = x_dtype == MOE_BF16;
     const size_t esz = bf ? 2 : 4;
     const void* xs = (const char*)x + (size_t)mp_idx * S * M * esz;
-    if (E <= 16) {
+    if (E <= 16 && bf && S >= 8192 && (uint64_t)S * (uint64_t)M * 2 <= 0xFFFFFFF0ull) {
+      // fp64 matrix cores; TW token waves (32 tokens each) per block so that the grid has about two blocks per
+      // compute unit or more
+      const int tw = S >= 512 * 4 * 32 ? 4 : S >= 512 * 2 * 32 ? 2 : 1;
+      const int64_t tpb = (int64_t)tw * G4_NS * G4_TS;     // tokens per block
+      const dim3 grid((unsigned)((S + tpb - 1) / tpb)), block(64 * tw * G4_KW);
+      const bf16_t* xb = (const bf16_t*)xs;
+#define LAUNCH_M4(np, tw_) hipLaunchKernelGGL((gate_logits_mfma4<np, tw_>), grid, block, 0, st, xb, Wg, gate_bias, logits, S, M, E)
+#define LAUNCH_M4_TW(np) do { if (tw == 4) LAUNCH_M4(np, 4); else if (tw == 2) LAUNCH_M4(np, 2); else LAUNCH_M4(np, 1); } while (0)
+      if (E <= 4) LAUNCH_M4_TW(1); else if (E <= 8) LAUNCH_M4_TW(2); else LAUNCH_M4_TW(4);
+#undef LAUNCH_M4_TW
+#undef LAUNCH_M4
+    } else if (E <= 16) {
       const int EC = E <= 8 ? 8 : 16;
       const int T = E <= 8 ? 4 : 2;
       // many tokens: 8-wave blocks halve the Wg staging work per token; few tokens: 4-wave blocks fill the chip

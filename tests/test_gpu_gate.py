@@ -109,3 +109,23 @@ def test_gate_logits_odd_shapes(E, M, dtype):
     assert rel_err(got["logits"], ref) <= 1e-6
     if (got["logits"].astype(np.float32) == ref).all():
         check_routing(got, ref, k, 50, 1)
+
+
+@pytest.mark.parametrize("S,E,M,n_mp", [(9000, 12, 200, 1), (20001, 7, 1096, 1), (35000, 16, 520, 2), (70001, 3, 72, 1),
+                                        (16384, 8, 1024, 1), (8192, 9, 64, 1)])
+def test_gate_logits_many_tokens(S, E, M, n_mp):
+    """bf16 activations, at most 16 experts, many tokens: the logits kernel on the 4-block fp64 matrix cores, with
+    every block size it is launched with, token counts off every tile, and M off the 64- and 512-wide steps."""
+    k = min(E, 2)
+    rng = np.random.default_rng(S + E)
+    x = synth.store(rng.standard_normal((S * n_mp, M)).astype(np.float32), "bf16")
+    Wg = (rng.standard_normal((M, E)) * 0.3).astype(np.float32)
+    bias = rng.standard_normal(E).astype(np.float32)
+    C = O.capacity(S, E, k, 1.0)
+    got = run_gate(None, k, C, 1, x=to_dev(x), Wg=to_dev(Wg), bias=to_dev(bias), S_total=S * n_mp, mp=(n_mp - 1, n_mp), M=M)
+    ref = O.gate_logits(x.val[(n_mp - 1) * S:], Wg, bias)
+    assert rel_err(got["logits"], ref) <= 1e-6
+    same = got["logits"].astype(np.float32) == ref
+    assert same.mean() > 0.9999
+    if same.all():
+        check_routing(got, ref, k, C, 1)
